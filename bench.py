@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the CUSA decode hot path on one MI355X.
+
+A "step" is the attention part of one decode step of the paper's Alg. 1 over all layers of
+the workload: full-attention layers, the selection layer (full attention + scoring + per-head
+top-k + cross-head union + window) and the sparse-attention layers that reuse rho.  Inputs are
+seeded, synthetic and resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+
+Prints ONE JSON line: the step time, a `roofline` object for the kernel that takes most of the
+step (algorithmic bytes / its HIP-event duration against the 8 TB/s HBM peak), per-kernel
+figures, the speedup over this library's own full attention on every layer, and `cpu_baseline`,
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the HIP-event pass (use under rocprofv3 to keep the trace to the timed steps)")
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_bytes(w, lens, acc):
+    """Algorithmic bytes of ONE launch of each bandwidth-bound kernel (all sequences of the batch)."""
+    G, K, W = w.n_kv_heads, w.budget, w.window
+    return {
+        "attn_partial_kernel<full>": sum(acc.full_attn_bytes(G, L) for L in lens),
+        "attn_partial_kernel<sparse>": sum(acc.sparse_attn_bytes(G, K, L) for L in lens),
+        "score_kernel": sum(acc.score_bytes(G, L, K, W) for L in lens),
+    }
+
+
+def cpu_baseline(inp, w, sched):
+    """Oracle wall time for one step, extrapolated from one layer of each kind on sequence 0."""
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import host_view
+    sel = sched.index(1)
+    q, K, V = host_view(inp, sel, 0)
+    t0 = time.perf_counter()
+    oracle.attention(q, K, V)
+    t_full = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    rho = oracle.select(q, K, w.budget, w.window, w.topk_per_head)
+    t_sel = time.perf_counter() - t0
+    sp = sched.index(2)
+    q, K, V = host_view(inp, sp, 0)
+    t0 = time.perf_counter()
+    oracle.attention(q, K, V, rho)
+    t_sparse = time.perf_counter() - t0
+    n_full = sum(1 for k in sched if k in (0, 1))
+    n_sparse = sum(1 for k in sched if k == 2)
+    scale = sum(inp.seq_lens_host) / inp.seq_lens_host[0]          # other sequences, by length
+    step_s = (n_full * t_full + t_sel) * scale + n_sparse * t_sparse * w.batch
+    return {
+        "value": step_s * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"sequence 0 of {w.batch}: one full-attention layer ({t_full:.3f} s), one selection "
+                   f"({t_sel:.3f} s), one sparse layer ({t_sparse:.4f} s); scaled to {n_full} full + 1 select + "
+                   f"{n_sparse} sparse layers and to all sequences by length"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the hot path shards by sequence "
+              "and KV head without communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    from paper_2508_07101_amd import accounting as acc
+    from paper_2508_07101_amd import binding as cb
+    from paper_2508_07101_amd import workloads as wl
+    from paper_2508_07101_amd.runner import StepRunner
+
+    w = wl.WORKLOADS[args.workload]
+    inp = wl.make_inputs(w, "cuda:0")
+    sched = list(w.schedule)
+    lens = inp.seq_lens_host
+    r = StepRunner(inp, sched)
+    torch.cuda.synchronize()
+
+    step_s = time_steps(r.run, args.steps, args.warmup, torch)
+
+    full_s = None
+    if not args.no_full_baseline:
+        rf = StepRunner(inp, [0] * len(sched))
+        full_s = time_steps(rf.run, max(3, args.steps // 4), 1, torch)
+        del rf
+
+    kernels, roofline = {}, None
+    if not args.no_kernel_timing:
+        cb.profile_reset()
+        cb.profile_enable(True)
+        for _ in range(args.steps):
+            r.run()
+        torch.cuda.synchronize()
+        prof = cb.profile_read()
+        cb.profile_enable(False)
+        kb = kernel_bytes(w, lens, acc)
+        for name, p in prof.items():
+            if p["calls"] == 0:
+                continue
+            avg_us = p["total_ms"] * 1e3 / p["calls"]
+            k = {"launches_per_step": p["calls"] // args.steps, "avg_us": round(avg_us, 3),
+                 "us_per_step": round(p["total_ms"] * 1e3 / args.steps, 3)}
+            if name in kb and kb[name] > 0:
+                k["bytes_per_launch"] = kb[name]
+                k["achieved_GBs"] = round(kb[name] / (avg_us * 1e-6) / 1e9, 1)
+                k["frac_of_hbm_peak"] = round(k["achieved_GBs"] / HBM_PEAK_GBS, 4)
+            kernels[name] = k
+        hot = max((n for n in kernels if "achieved_GBs" in kernels[n]), key=lambda n: kernels[n]["us_per_step"])
+        roofline = {"kernel": hot, "bound": "hbm", "achieved": kernels[hot]["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": kernels[hot]["frac_of_hbm_peak"], "traffic": None,
+                    "bytes_per_launch": kernels[hot]["bytes_per_launch"], "avg_us": kernels[hot]["avg_us"]}
+
+    sb = acc.step_bytes(sched, lens, w.n_kv_heads, w.budget, w.window)
+    out = {
+        "metric": "us_per_decode_step_select_plus_sparse_attn",
+        "value": round(step_s * 1e6, 2), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_s * 1e3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads}q/{w.n_kv_heads}kv heads, "
+                               f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
+                               f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
+                   "schedule": "".join("FSs"[k] for k in sched)},
+        "step_algorithmic_bytes": sb["total"],
+        "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if full_s is not None:
+        out["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
+        out["speedup_vs_full_attention"] = round(full_s / step_s, 3)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, w, sched)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,172 @@
+/*
+ * libcusa -- decode-time hot path of Cross-Head Unified Sparse Attention (CUSA,
+ * "LessIsMore", arXiv 2508.07101) for AMD MI355X (gfx950).
+ *
+ * One decode step of the attention part of the paper's Alg. 1: full attention
+ * layers, a token-selection layer that turns per-head top-k picks into ONE
+ * token set rho shared by all heads (Sec. 3.2) plus a recency window (Sec. 3.3),
+ * and sparse-attention layers that reuse rho (Sec. 3.1, 3.4).
+ *
+ * Conventions for every entry point
+ *  - "host" pointers are read during the call and may be freed afterwards;
+ *    "device" pointers are GPU memory owned by the caller and must stay valid
+ *    until the work enqueued on `stream` has finished.
+ *  - Calls only ENQUEUE kernels on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream).  They never allocate, free or synchronise, so
+ *    a caller may capture them into a HIP graph.
+ *  - Argument errors are detected on the host before anything is enqueued and
+ *    returned as a cusa_status; no C++ exception crosses this boundary.  A
+ *    failed kernel launch returns CUSA_ERR_LAUNCH.
+ *  - q, K, V and outputs are bf16 (IEEE-like, 8-bit exponent, 8-bit
+ *    significand); scores and softmax run in binary32; indices are int32.
+ *  - head_dim must be 128; n_q_heads / n_kv_heads (the GQA group g) must be
+ *    1, 2, 4 or 8; a paged cache must use 16-token pages.
+ */
+#ifndef CUSA_H
+#define CUSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CUSA_OK = 0,
+    CUSA_ERR_INVALID_ARG = 1,        /* NULL pointer, bad shape, inconsistent sizes        */
+    CUSA_ERR_UNSUPPORTED = 2,        /* valid request this build has no kernel for         */
+    CUSA_ERR_WORKSPACE_TOO_SMALL = 3,
+    CUSA_ERR_LAUNCH = 4              /* the HIP runtime refused a launch                   */
+} cusa_status;
+
+/* Layer kinds of Alg. 1's per-layer branch. */
+typedef enum { CUSA_LAYER_FULL = 0, CUSA_LAYER_SELECT = 1, CUSA_LAYER_SPARSE = 2 } cusa_layer_kind;
+
+typedef enum { CUSA_KV_CONTIGUOUS = 0, CUSA_KV_PAGED = 1 } cusa_kv_layout;
+
+/* Reading of "globally ranked" in Sec. 3.2 (the paper names no ranking key).
+ * FIRST_OCCURRENCE: flatten the per-head ranked lists rank-major (all rank-0
+ * picks in head order, then all rank-1 picks, ...), drop repeats, keep the
+ * first K-W tokens.  The other two are reserved values: this build returns
+ * CUSA_ERR_UNSUPPORTED for them. */
+typedef enum { CUSA_RANK_FIRST_OCCURRENCE = 0, CUSA_RANK_VOTES = 1, CUSA_RANK_MAX_SCORE = 2 } cusa_rank_mode;
+
+/* Problem statement of Alg. 1 ("token budget K, static ratio r"), host memory. */
+typedef struct {
+    int32_t batch;          /* B sequences, each with its own rho                              */
+    int32_t n_q_heads;      /* H                                                               */
+    int32_t n_kv_heads;     /* G, divides H                                                    */
+    int32_t head_dim;       /* d = 128                                                         */
+    int32_t budget;         /* K: tokens attended by a sparse layer, window included           */
+    int32_t window;         /* W = K*r most recent tokens always kept, 0 <= W <= K             */
+    int32_t topk_per_head;  /* k picks proposed per head; 0 means K-W; K-W <= k <= 8192        */
+    int32_t n_sink;         /* reserved, must be 0                                             */
+    int32_t rank_mode;      /* cusa_rank_mode                                                  */
+    float   sm_scale;       /* softmax scale of Eq. 1, normally 1/sqrt(d)                      */
+} cusa_params;
+
+/* One layer's KV cache view, host memory; the pointers inside are device memory.
+ * contiguous: element (b, kv, t, i) of K is k[b*stride_batch + kv*stride_head +
+ *             t*stride_token + i] (strides in elements, stride_token >= 128 and a
+ *             multiple of 8 so rows are 16-byte aligned); V uses the same strides.
+ * paged:      pools are [n_pages][n_kv_heads][page_size][128]; logical token t of
+ *             sequence b lives in pool page block_table[b*max_pages + t/page_size],
+ *             slot t % page_size.
+ * seq_lens[b] = L_b >= 1 counts the token appended in this step (Alg. 1 appends
+ * before attending); max_seq_len is a host-side bound L_b <= max_seq_len used
+ * to size grids and workspace. */
+typedef struct {
+    const void*    k;
+    const void*    v;
+    int32_t        layout;          /* cusa_kv_layout */
+    int64_t        stride_batch, stride_head, stride_token;
+    const int32_t* block_table;     /* device, [batch][max_pages]; paged only */
+    int32_t        max_pages;
+    int32_t        page_size;       /* 16 */
+    int64_t        n_pages;
+    const int32_t* seq_lens;        /* device, [batch] */
+    int32_t        max_seq_len;
+} cusa_kv;
+
+/* Where the selection intermediates live inside the workspace after cusa_select
+ * (byte offsets from the workspace base), so that a test can read them back:
+ *   scores    float  [batch][n_q_heads][ld_scores]   P = q.K^T over [0, L_b-W)
+ *   rho_head  int32  [batch][k][n_q_heads]           ranked picks, RANK-MAJOR:
+ *             entry (b, j, h) is head h's rank-j pick; valid for j < min(k, L_b-W)
+ * Both are defined only for sequences with L_b > K. */
+typedef struct {
+    size_t  scores_offset;
+    int64_t ld_scores;
+    size_t  rho_head_offset;
+    int32_t k;                      /* topk_per_head after resolving 0 -> K-W */
+    size_t  total_bytes;
+} cusa_ws_layout;
+
+/* Bytes of device workspace any of the calls below needs for `params` and
+ * sequences up to max_seq_len.  Workspace must be 256-byte aligned; its content
+ * need not be preserved between calls.  Error: INVALID_ARG. */
+cusa_status cusa_workspace_bytes(const cusa_params* params, int32_t max_seq_len, size_t* bytes);
+cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len, cusa_ws_layout* layout);
+
+/* Token selection of a selection layer (Alg. 1, the lines that build rho;
+ * Sec. 3.2 and 3.3).  For each sequence b with L = seq_lens[b]:
+ *   L <= K : rho = {0 .. L-1}
+ *   else   : P = q.K^T (unscaled, binary32, summed left to right over d) for
+ *            tokens [0, L-W); every head ranks its min(k, L-W) best tokens by
+ *            (score descending, position ascending); the ranked lists are
+ *            unified per rank_mode and the first K-W distinct tokens kept;
+ *            the last W positions are added.
+ * q    device bf16 [batch][n_q_heads][128], this layer's query.
+ * idx  device int32 [batch][budget]: rho ascending; entries >= cnt[b] unspecified.
+ * cnt  device int32 [batch]: |rho| = min(K, L_b).
+ * Errors: INVALID_ARG, UNSUPPORTED (rank_mode), WORKSPACE_TOO_SMALL, LAUNCH. */
+cusa_status cusa_select(const cusa_params* params, const void* q, const cusa_kv* kv,
+                        int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream);
+
+/* SparseAttention(q, C[rho]) of Alg. 1: Eq. 1 restricted to the positions
+ * idx[b][0 .. cnt[b]) (the same set for every head), on this layer's own K/V.
+ * idx entries must lie in [0, seq_lens[b]); cnt[b] in [1, budget].
+ * out  device bf16 [batch][n_q_heads][128]. */
+cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cusa_kv* kv,
+                             const int32_t* idx, const int32_t* cnt, void* out,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* FullAttention(q, C[:]) of Alg. 1 (Eq. 1 over all L_b tokens); also the
+ * baseline the sparse path is compared with.  budget/window/topk are ignored. */
+cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv,
+                           void* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Attention part of one decode step of Alg. 1 over n_layers layers.
+ * layer_kind  host int32[n_layers] of cusa_layer_kind.  FULL: full attention.
+ *             SELECT: full attention for this layer's output, then rho is rebuilt
+ *             from this layer's q and K.  SPARSE: sparse attention over the
+ *             current rho.  A SPARSE layer with no SELECT layer before it in this
+ *             call is INVALID_ARG (Alg. 1 starts with rho empty).
+ * q_layers    host array of n_layers device pointers, each bf16 [batch][H][128].
+ * kv_layers   host array of n_layers cache views.
+ * out_layers  host array of n_layers device pointers, each bf16 [batch][H][128].
+ * idx, cnt    device, as in cusa_select; hold the latest rho on return. */
+cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const int32_t* layer_kind,
+                             const void* const* q_layers, const cusa_kv* kv_layers,
+                             void* const* out_layers, int32_t* idx, int32_t* cnt,
+                             void* ws, size_t ws_bytes, void* stream);
+
+const char* cusa_strerror(cusa_status status);
+
+/* ---- per-kernel timing (benchmark support; not part of the method) ---------
+ * While enabled, every kernel the library enqueues is bracketed by HIP events
+ * on the launch stream.  cusa_profile_read waits for those events and returns,
+ * for kernel id i < n, the number of launches and the summed milliseconds since
+ * the last reset.  Enabling costs host time per launch and creates events, so it
+ * must not be on under graph capture.  Returns the number of kernel ids. */
+int32_t     cusa_profile_num_kernels(void);
+const char* cusa_profile_kernel_name(int32_t id);
+void        cusa_profile_enable(int32_t on);
+void        cusa_profile_reset(void);
+cusa_status cusa_profile_read(int32_t n, int64_t* calls, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CUSA_H */

@@ -1,0 +1,474 @@
+// Host side of libcusa: argument checks, workspace layout, launch geometry and
+// the per-layer walk of Alg. 1.  Everything here only enqueues kernels on the
+// caller's stream; nothing allocates device memory or synchronises.
+#include "../../include/cusa.h"
+
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+#include <vector>
+
+#include "cusa_kernels.hpp"
+
+using namespace cusa;
+
+namespace {
+
+// ------------------------------------------------------------------ profiling
+
+enum KernelId { KID_QF32 = 0, KID_SCORE, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_COUNT };
+const char* const kKernelNames[KID_COUNT] = {"q_to_f32_kernel", "score_kernel", "topk_kernel", "union_kernel",
+                                             "attn_partial_kernel<full>", "attn_partial_kernel<sparse>",
+                                             "attn_reduce_kernel"};
+
+struct ProfRec {
+    int id;
+    hipEvent_t start, stop;
+};
+struct Profiler {
+    std::mutex mu;
+    bool on = false;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> pool;
+    int64_t calls[KID_COUNT] = {0};
+    double ms[KID_COUNT] = {0};
+} g_prof;
+
+hipEvent_t prof_event() {
+    if (!g_prof.pool.empty()) {
+        hipEvent_t e = g_prof.pool.back();
+        g_prof.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+struct ProfScope {
+    ProfRec rec;
+    hipStream_t stream;
+    bool active;
+    ProfScope(int id, hipStream_t s) : stream(s), active(g_prof.on) {
+        if (!active) return;
+        std::lock_guard<std::mutex> lk(g_prof.mu);
+        rec.id = id;
+        rec.start = prof_event();
+        rec.stop = prof_event();
+        (void)hipEventRecord(rec.start, stream);
+    }
+    ~ProfScope() {
+        if (!active) return;
+        (void)hipEventRecord(rec.stop, stream);
+        std::lock_guard<std::mutex> lk(g_prof.mu);
+        g_prof.recs.push_back(rec);
+    }
+};
+
+// ------------------------------------------------------------------ validation
+
+bool valid_group(int g) { return g == 1 || g == 2 || g == 4 || g == 8; }
+
+int resolved_k(const cusa_params* p) { return p->topk_per_head > 0 ? p->topk_per_head : p->budget - p->window; }
+
+cusa_status check_params(const cusa_params* p, bool need_budget) {
+    if (!p) return CUSA_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1) return CUSA_ERR_INVALID_ARG;
+    if (p->n_q_heads % p->n_kv_heads != 0) return CUSA_ERR_INVALID_ARG;
+    if (p->head_dim != D) return CUSA_ERR_UNSUPPORTED;
+    if (!valid_group(p->n_q_heads / p->n_kv_heads)) return CUSA_ERR_UNSUPPORTED;
+    if (p->batch > 65535 || p->n_q_heads > 65535) return CUSA_ERR_UNSUPPORTED;
+    if (!(p->sm_scale > 0.0f) || !(p->sm_scale < 1e30f)) return CUSA_ERR_INVALID_ARG;
+    if (need_budget) {
+        if (p->budget < 1 || p->window < 0 || p->window > p->budget) return CUSA_ERR_INVALID_ARG;
+        if (p->topk_per_head < 0) return CUSA_ERR_INVALID_ARG;
+        if (p->n_sink != 0) return CUSA_ERR_UNSUPPORTED;
+        if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {
+            if (p->rank_mode == CUSA_RANK_VOTES || p->rank_mode == CUSA_RANK_MAX_SCORE) return CUSA_ERR_UNSUPPORTED;
+            return CUSA_ERR_INVALID_ARG;
+        }
+        const int k = resolved_k(p);
+        if (k < p->budget - p->window) return CUSA_ERR_INVALID_ARG;
+        if (k > 8192) return CUSA_ERR_UNSUPPORTED;
+    }
+    return CUSA_OK;
+}
+
+cusa_status check_kv(const cusa_params* p, const cusa_kv* kv) {
+    if (!kv || !kv->k || !kv->v || !kv->seq_lens) return CUSA_ERR_INVALID_ARG;
+    if (kv->max_seq_len < 1) return CUSA_ERR_INVALID_ARG;
+    if (((uintptr_t)kv->k | (uintptr_t)kv->v) & 15) return CUSA_ERR_INVALID_ARG;
+    if (kv->layout == CUSA_KV_CONTIGUOUS) {
+        if (kv->stride_token < D || (kv->stride_token & 7) || (kv->stride_head & 7) || (kv->stride_batch & 7))
+            return CUSA_ERR_INVALID_ARG;
+        if (kv->stride_head < 0 || kv->stride_batch < 0) return CUSA_ERR_INVALID_ARG;
+    } else if (kv->layout == CUSA_KV_PAGED) {
+        if (kv->page_size != PAGE) return CUSA_ERR_UNSUPPORTED;
+        if (!kv->block_table || kv->n_pages < 1) return CUSA_ERR_INVALID_ARG;
+        if ((int64_t)kv->max_pages * PAGE < kv->max_seq_len) return CUSA_ERR_INVALID_ARG;
+    } else {
+        return CUSA_ERR_INVALID_ARG;
+    }
+    (void)p;
+    return CUSA_OK;
+}
+
+KvView make_view(const cusa_params* p, const cusa_kv* kv) {
+    KvView v;
+    v.k = static_cast<const uint16_t*>(kv->k);
+    v.v = static_cast<const uint16_t*>(kv->v);
+    v.sb = kv->stride_batch;
+    v.sh = kv->stride_head;
+    v.st = kv->stride_token;
+    v.bt = kv->block_table;
+    v.max_pages = kv->max_pages;
+    v.G = p->n_kv_heads;
+    v.seq_lens = kv->seq_lens;
+    return v;
+}
+
+// ------------------------------------------------------------------ workspace
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr int MAX_SPLITS = 256;
+constexpr int TARGET_WGS = 1024;
+
+struct AttnPlan {
+    int ti;        // row-load instructions per wave iteration (4 or 8)
+    int n_splits;
+};
+
+// Split count and tile depth for n_max tokens per (sequence, KV head).
+AttnPlan plan_attn(int n_max, int BG, int g) {
+    AttnPlan pl;
+    const int64_t tiles128 = ((int64_t)n_max + 127) / 128 * BG;
+    pl.ti = (g <= 4 && tiles128 >= 512) ? 8 : 4;
+    const int wg_tile = pl.ti * 4 * ATTN_WAVES;
+    int by_work = (n_max + wg_tile - 1) / wg_tile;
+    int target = TARGET_WGS / BG;
+    if (target < 1) target = 1;
+    int s = by_work < target ? by_work : target;
+    if (s < 1) s = 1;
+    if (s > MAX_SPLITS) s = MAX_SPLITS;
+    pl.n_splits = s;
+    return pl;
+}
+
+struct WsLayout {
+    size_t qf, scores, rho_head, first, part_acc, part_ml, total;
+    int64_t ldp;
+    int k;
+    int max_splits;
+};
+
+WsLayout make_layout(const cusa_params* p, int max_seq_len) {
+    WsLayout w;
+    const int64_t B = p->batch, H = p->n_q_heads;
+    const int BG = p->batch * p->n_kv_heads, g = p->n_q_heads / p->n_kv_heads;
+    int64_t lc = (int64_t)max_seq_len - p->window;
+    if (lc < 1) lc = 1;
+    w.ldp = (lc + 63) / 64 * 64;
+    w.k = resolved_k(p);
+    if (w.k < 1) w.k = 1;
+    int ms = plan_attn(max_seq_len, BG, g).n_splits;
+    int ms2 = plan_attn(p->budget > 0 ? p->budget : 1, BG, g).n_splits;
+    w.max_splits = ms > ms2 ? ms : ms2;
+    size_t off = 0;
+    w.qf = off;        off += align256((size_t)(B * H * D) * 4);
+    w.scores = off;    off += align256((size_t)(B * H * w.ldp) * 4);
+    w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);
+    w.first = off;     off += align256((size_t)(B * w.ldp) * 4);
+    w.part_acc = off;  off += align256((size_t)(B * H * w.max_splits * D) * 4);
+    w.part_ml = off;   off += align256((size_t)(B * H * w.max_splits * 2) * 4);
+    w.total = off;
+    return w;
+}
+
+cusa_status check_ws(const WsLayout& w, void* ws, size_t ws_bytes) {
+    if (!ws || ((uintptr_t)ws & 255)) return CUSA_ERR_INVALID_ARG;
+    if (ws_bytes < w.total) return CUSA_ERR_WORKSPACE_TOO_SMALL;
+    return CUSA_OK;
+}
+
+template <typename T>
+T* ws_ptr(void* ws, size_t off) {
+    return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
+}
+
+cusa_status launch_status() { return hipGetLastError() == hipSuccess ? CUSA_OK : CUSA_ERR_LAUNCH; }
+
+// ------------------------------------------------------------------ launches
+
+template <int GQ, int TI, bool SPARSE>
+void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
+                         const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
+                         int n_splits, int H) {
+    if (paged)
+        attn_partial_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, n_splits, H);
+    else
+        attn_partial_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, n_splits, H);
+}
+
+template <int GQ, bool SPARSE>
+void launch_attn_ti(int ti, bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
+                    const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
+                    int n_splits, int H) {
+    if constexpr (GQ <= 4) {
+        if (ti == 8) {
+            launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, n_splits, H);
+            return;
+        }
+    }
+    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, n_splits, H);
+}
+
+// Attention over all tokens (idx == nullptr) or over idx/cnt; n_max bounds the token count.
+template <bool SPARSE>
+cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv, const int32_t* idx,
+                          const int32_t* cnt, int n_max, void* out, void* ws, const WsLayout& w, hipStream_t s) {
+    const int g = p->n_q_heads / p->n_kv_heads, BG = p->batch * p->n_kv_heads, H = p->n_q_heads;
+    const AttnPlan pl = plan_attn(n_max, BG, g);
+    if (pl.n_splits > w.max_splits) return CUSA_ERR_WORKSPACE_TOO_SMALL;
+    const KvView view = make_view(p, kv);
+    const bool paged = kv->layout == CUSA_KV_PAGED;
+    const float scale = p->sm_scale * 1.4426950408889634f;
+    float* pa = ws_ptr<float>(ws, w.part_acc);
+    float* pm = ws_ptr<float>(ws, w.part_ml);
+    const uint16_t* qq = static_cast<const uint16_t*>(q);
+    dim3 grid(pl.n_splits, p->n_kv_heads, p->batch);
+    {
+        ProfScope ps(SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL, s);
+        switch (g) {
+            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, pl.n_splits, H); break;
+            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, pl.n_splits, H); break;
+            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, pl.n_splits, H); break;
+            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, pl.n_splits, H); break;
+        }
+    }
+    if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+    {
+        ProfScope ps(KID_REDUCE, s);
+        attn_reduce_kernel<<<dim3(H, p->batch), D, 0, s>>>(pa, pm, static_cast<uint16_t*>(out), pl.n_splits, H);
+    }
+    return launch_status();
+}
+
+template <int GQ>
+void launch_score(bool paged, dim3 grid, hipStream_t s, const KvView& view, const float* qf, float* P, int64_t ldp,
+                  int H, int budget, int window) {
+    if (paged)
+        score_kernel<GQ, true><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window);
+    else
+        score_kernel<GQ, false><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window);
+}
+
+cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
+                       const WsLayout& w, hipStream_t s) {
+    const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
+    const KvView view = make_view(p, kv);
+    const bool paged = kv->layout == CUSA_KV_PAGED;
+    float* qf = ws_ptr<float>(ws, w.qf);
+    float* P = ws_ptr<float>(ws, w.scores);
+    int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
+    int32_t* first = ws_ptr<int32_t>(ws, w.first);
+
+    if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
+        const int nq = B * H * D;
+        {
+            ProfScope ps(KID_QF32, s);
+            q_to_f32_kernel<<<(nq + 255) / 256, 256, 0, s>>>(static_cast<const uint16_t*>(q), qf, nq);
+        }
+        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+        const int lc_max = kv->max_seq_len - p->window;
+        dim3 grid((lc_max + SCORE_ROWS - 1) / SCORE_ROWS, p->n_kv_heads, B);
+        {
+            ProfScope ps(KID_SCORE, s);
+            switch (g) {
+                case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
+                case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
+                case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
+                default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
+            }
+        }
+        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+        int nsort = 1024;
+        while (nsort < w.k) nsort <<= 1;
+        const size_t shmem = (size_t)nsort * sizeof(uint64_t);
+        if (shmem > 48 * 1024) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem) != hipSuccess)
+                return CUSA_ERR_LAUNCH;
+        }
+        {
+            ProfScope ps(KID_TOPK, s);
+            topk_kernel<<<dim3(H, B), SEL_THREADS, shmem, s>>>(P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget,
+                                                               p->window, nsort);
+        }
+        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+    }
+    {
+        ProfScope ps(KID_UNION, s);
+        union_kernel<<<B, SEL_THREADS, 0, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k, p->budget,
+                                               p->window);
+    }
+    return launch_status();
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+cusa_status cusa_workspace_bytes(const cusa_params* params, int32_t max_seq_len, size_t* bytes) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if (!bytes || max_seq_len < 1) return CUSA_ERR_INVALID_ARG;
+    *bytes = make_layout(params, max_seq_len).total;
+    return CUSA_OK;
+}
+
+cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len, cusa_ws_layout* layout) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if (!layout || max_seq_len < 1) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, max_seq_len);
+    layout->scores_offset = w.scores;
+    layout->ld_scores = w.ldp;
+    layout->rho_head_offset = w.rho_head;
+    layout->k = w.k;
+    layout->total_bytes = w.total;
+    return CUSA_OK;
+}
+
+cusa_status cusa_select(const cusa_params* params, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt,
+                        void* ws, size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx || !cnt || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    return run_select(params, q, kv, idx, cnt, ws, w, static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cusa_kv* kv, const int32_t* idx,
+                             const int32_t* cnt, void* out, void* ws, size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx || !cnt || !out || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
+    return run_attention<true>(params, q, kv, idx, cnt, n_max, out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv, void* out, void* ws,
+                           size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !out || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    return run_attention<false>(params, q, kv, nullptr, nullptr, kv->max_seq_len, out, ws, w,
+                                static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const int32_t* layer_kind,
+                             const void* const* q_layers, const cusa_kv* kv_layers, void* const* out_layers,
+                             int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if (n_layers < 1 || !layer_kind || !q_layers || !kv_layers || !out_layers || !idx || !cnt)
+        return CUSA_ERR_INVALID_ARG;
+    int max_len = 0;
+    bool have_rho = false;
+    for (int i = 0; i < n_layers; ++i) {
+        if ((st = check_kv(params, &kv_layers[i])) != CUSA_OK) return st;
+        if (!q_layers[i] || !out_layers[i] || ((uintptr_t)q_layers[i] & 15)) return CUSA_ERR_INVALID_ARG;
+        if (kv_layers[i].max_seq_len > max_len) max_len = kv_layers[i].max_seq_len;
+        switch (layer_kind[i]) {
+            case CUSA_LAYER_FULL: break;
+            case CUSA_LAYER_SELECT: have_rho = true; break;
+            case CUSA_LAYER_SPARSE:
+                if (!have_rho) return CUSA_ERR_INVALID_ARG;
+                break;
+            default: return CUSA_ERR_INVALID_ARG;
+        }
+    }
+    const WsLayout w = make_layout(params, max_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int i = 0; i < n_layers; ++i) {
+        const cusa_kv* kv = &kv_layers[i];
+        if (layer_kind[i] == CUSA_LAYER_SPARSE) {
+            const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
+            st = run_attention<true>(params, q_layers[i], kv, idx, cnt, n_max, out_layers[i], ws, w, s);
+        } else {
+            st = run_attention<false>(params, q_layers[i], kv, nullptr, nullptr, kv->max_seq_len, out_layers[i], ws,
+                                      w, s);
+            if (st == CUSA_OK && layer_kind[i] == CUSA_LAYER_SELECT)
+                st = run_select(params, q_layers[i], kv, idx, cnt, ws, w, s);
+        }
+        if (st != CUSA_OK) return st;
+    }
+    return CUSA_OK;
+}
+
+const char* cusa_strerror(cusa_status status) {
+    switch (status) {
+        case CUSA_OK: return "ok";
+        case CUSA_ERR_INVALID_ARG: return "invalid argument";
+        case CUSA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case CUSA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case CUSA_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int32_t cusa_profile_num_kernels(void) { return KID_COUNT; }
+
+const char* cusa_profile_kernel_name(int32_t id) { return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : ""; }
+
+void cusa_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.on = on != 0;
+}
+
+static void prof_drain_locked() {
+    for (const ProfRec& r : g_prof.recs) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            g_prof.calls[r.id] += 1;
+            g_prof.ms[r.id] += ms;
+        }
+        g_prof.pool.push_back(r.start);
+        g_prof.pool.push_back(r.stop);
+    }
+    g_prof.recs.clear();
+}
+
+void cusa_profile_reset(void) {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    prof_drain_locked();
+    for (int i = 0; i < KID_COUNT; ++i) {
+        g_prof.calls[i] = 0;
+        g_prof.ms[i] = 0.0;
+    }
+}
+
+cusa_status cusa_profile_read(int32_t n, int64_t* calls, double* total_ms) {
+    if (n < 0 || !calls || !total_ms) return CUSA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    prof_drain_locked();
+    for (int i = 0; i < n && i < KID_COUNT; ++i) {
+        calls[i] = g_prof.calls[i];
+        total_ms[i] = g_prof.ms[i];
+    }
+    return CUSA_OK;
+}
+
+}  // extern "C"

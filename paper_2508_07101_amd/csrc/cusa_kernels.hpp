@@ -1,0 +1,649 @@
+// Device code of libcusa: gfx950 kernels for the CUSA decode hot path.
+//
+//   q_to_f32_kernel     widen q to binary32 so the scoring kernel can read it
+//                       through the scalar cache
+//   score_kernel        P = q.K^T over the candidate range (Alg. 1, selection
+//                       layer), one lane per key row, K staged through LDS
+//   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on
+//                       order-preserving keys, then a bitonic sort in LDS
+//   union_kernel        cross-head union, first-occurrence global rank, cut at
+//                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
+//   attn_partial_kernel split-K flash-decode over all tokens or over rho
+//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers
+//   attn_reduce_kernel  merges the split-K partials and writes bf16
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cusa {
+
+constexpr int D = 128;        // head_dim
+constexpr int PAGE = 16;      // tokens per page of a paged cache
+
+struct KvView {
+    const uint16_t* k;
+    const uint16_t* v;
+    int64_t sb, sh, st;       // contiguous: element strides (batch, kv head, token)
+    const int32_t* bt;        // paged: block table [B][max_pages]
+    int32_t max_pages;
+    int32_t G;                // kv heads
+    const int32_t* seq_lens;  // [B]
+};
+
+template <bool PAGED>
+__device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int kvh, int pos) {
+    if (PAGED) {
+        int64_t page = kv.bt[(int64_t)b * kv.max_pages + (pos >> 4)];
+        return ((page * kv.G + kvh) * PAGE + (pos & (PAGE - 1))) * D;
+    }
+    return (int64_t)b * kv.sb + (int64_t)kvh * kv.sh + (int64_t)pos * kv.st;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ void unpack8(const uint4& w, float* f) {
+    f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
+    f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+    f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z);
+    f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;   // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------- q -> binary32
+
+__global__ void q_to_f32_kernel(const uint16_t* __restrict__ q, float* __restrict__ qf, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) qf[i] = __uint_as_float((uint32_t)q[i] << 16);
+}
+
+// ---------------------------------------------------------------- scoring pass
+//
+// One workgroup scores 256 consecutive candidate keys of one KV head against the
+// GQ query heads of its group.  The 64 KB tile is fetched with coalesced 16-byte
+// loads (16 lanes per 256-byte row) and parked in LDS; then every lane owns one
+// row and runs the left-to-right binary32 FMA chain over the 128 elements, the
+// summation order the selection's bit-exactness rests on (a bf16*bf16 product is
+// exact in binary32, so fma(q,k,acc) rounds once, like acc + q*k).  q comes from
+// the scalar cache (wave-uniform addresses), so the inner loop is pure FMA.
+// LDS chunk c of row r sits at slot c ^ (r & 7): row reads by consecutive lanes
+// then fall into distinct 16-byte bank groups.
+
+constexpr int SCORE_ROWS = 256;
+
+template <int GQ, bool PAGED>
+__global__ __launch_bounds__(256) void score_kernel(KvView kv, const float* __restrict__ qf,
+                                                     float* __restrict__ P, int64_t ldp, int H,
+                                                     int budget, int window) {
+    __shared__ uint4 tile[SCORE_ROWS * 16];
+    const int b = blockIdx.z, kvh = blockIdx.y, tid = threadIdx.x;
+    const int L = kv.seq_lens[b];
+    if (L <= budget) return;                      // rho = everything, nothing to score
+    const int Lc = L - window;
+    const int t0 = blockIdx.x * SCORE_ROWS;
+    if (t0 >= Lc) return;
+
+    uint4 stage[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int chunk = i * 256 + tid;
+        const int row = chunk >> 4, c = chunk & 15;
+        const int t = t0 + row;
+        stage[i] = make_uint4(0, 0, 0, 0);
+        if (t < Lc) {
+            const uint16_t* p = kv.k + row_offset<PAGED>(kv, b, kvh, t) + c * 8;
+            stage[i] = *reinterpret_cast<const uint4*>(p);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int chunk = i * 256 + tid;
+        const int row = chunk >> 4, c = chunk & 15;
+        tile[row * 16 + (c ^ (row & 7))] = stage[i];
+    }
+    __syncthreads();
+
+    const float* __restrict__ qg = qf + ((int64_t)b * H + (int64_t)kvh * GQ) * D;
+    float acc[GQ];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) acc[h] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const uint4 w = tile[tid * 16 + (c ^ (tid & 7))];
+        float kf[8];
+        unpack8(w, kf);
+#pragma unroll
+        for (int h = 0; h < GQ; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h] = __builtin_fmaf(qg[h * D + c * 8 + e], kf[e], acc[h]);
+    }
+    const int t = t0 + tid;
+    if (t < Lc) {
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) P[((int64_t)b * H + kvh * GQ + h) * ldp + t] = acc[h];
+    }
+}
+
+// ---------------------------------------------------------------- block helpers
+
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// number of set bits of a 64-bit ballot below this lane
+__device__ __forceinline__ int mbcnt(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// Exclusive prefix sum of one int per thread over a 1024-thread block.
+// scratch: SEL_WAVES + 1 ints of LDS.  Returns the exclusive prefix; *total gets the sum.
+__device__ __forceinline__ int block_scan_excl(int v, int* scratch, int* total) {
+    const int lane = lane_id(), w = wave_id();
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(inc, o);
+        if (lane >= o) inc += n;
+    }
+    __syncthreads();                               // scratch may still be read from a previous call
+    if (lane == 63) scratch[w] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < SEL_WAVES; ++i) {
+            int c = scratch[i];
+            scratch[i] = run;
+            run += c;
+        }
+        scratch[SEL_WAVES] = run;
+    }
+    __syncthreads();
+    *total = scratch[SEL_WAVES];
+    return scratch[w] + inc - v;
+}
+
+// Order-preserving map of a binary32 score to uint32 (larger score -> larger key);
+// -0 is mapped like +0 so that the two compare equal.
+__device__ __forceinline__ uint32_t score_key(float s) {
+    uint32_t u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---------------------------------------------------------------- per-head top-k
+//
+// One 1024-thread workgroup per (sequence, head).  The candidates are ordered by
+// the 64-bit composite (score_key << 32 | ~position): larger composite = better
+// score, or equal score and lower position -- a strict total order, so "the k best"
+// is a unique set and a unique ranking.
+//   1. radix select (11/11/10-bit digits, LDS histograms) finds the score key T
+//      of the k-th best candidate and how many candidates tie with it;
+//   2. if more candidates equal T than are still needed, a second radix select
+//      over ~position finds the position bound among the ties;
+//   3. the k survivors are compacted into LDS and bitonic-sorted (descending);
+//   4. ranks are written rank-major: rho_head[b][j][h].
+
+struct SelectState {
+    uint32_t prefix;     // digits fixed so far
+    int need;            // how many of the candidates matching prefix are wanted
+    int count_eq;        // candidates whose digit equals the chosen one (last pass)
+};
+
+// One radix-select pass over `hist` (NB bins, already filled): choose the digit
+// in which the `need`-th largest lies.  All threads call; results via LDS `st`.
+template <int NB>
+__device__ __forceinline__ void pick_digit(int* hist, int* scratch, SelectState* st, int shift) {
+    // thread i owns bins [i*PER, i*PER+PER) counted from the top (descending digits)
+    constexpr int PER = (NB + SEL_THREADS - 1) / SEL_THREADS;
+    int local[PER];
+    int sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        int bin = NB - 1 - (threadIdx.x * PER + j);
+        local[j] = bin >= 0 ? hist[bin] : 0;
+        sum += local[j];
+    }
+    int total;
+    int above = block_scan_excl(sum, scratch, &total);   // candidates with larger digits
+    const int need = st->need;
+    __syncthreads();                                     // everyone has read st->need
+    if (above < need && need <= above + sum) {
+        int run = above;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (run < need && need <= run + local[j]) {
+                int bin = NB - 1 - (threadIdx.x * PER + j);
+                st->prefix |= (uint32_t)bin << shift;
+                st->need = need - run;
+                st->count_eq = local[j];
+            }
+            run += local[j];
+        }
+    }
+    __syncthreads();
+}
+
+// Radix select of the `need`-th largest 32-bit key among the n candidates for
+// which key_of(t, &key) returns true.  Leaves the key in st->prefix, the number
+// still wanted among equal keys in st->need, and their count in st->count_eq.
+template <typename KeyOf>
+__device__ __forceinline__ void radix_select(int n, int need, KeyOf key_of, int* hist, int* scratch,
+                                             SelectState* st) {
+    if (threadIdx.x == 0) {
+        st->prefix = 0;
+        st->need = need;
+        st->count_eq = 0;
+    }
+    const int shifts[3] = {21, 10, 0};
+    const int bits[3] = {11, 11, 10};
+    uint32_t mask = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
+        __syncthreads();
+        const uint32_t prefix = st->prefix;
+        const int shift = shifts[pass];
+        const uint32_t dmask = (1u << bits[pass]) - 1u;
+        for (int t = threadIdx.x; t < n; t += SEL_THREADS) {
+            uint32_t key;
+            if (key_of(t, &key) && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & dmask], 1);
+        }
+        __syncthreads();
+        if (pass < 2) pick_digit<2048>(hist, scratch, st, shift);
+        else pick_digit<1024>(hist, scratch, st, shift);
+        mask |= dmask << shift;
+    }
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
+                                                            const int32_t* __restrict__ seq_lens,
+                                                            int32_t* __restrict__ rho_head, int H, int k,
+                                                            int budget, int window, int nsort) {
+    extern __shared__ uint64_t sort_buf[];            // nsort composites; aliases the histogram
+    __shared__ int scratch[SEL_WAVES + 1];
+    __shared__ SelectState st;
+    __shared__ int n_out;
+    int* hist = reinterpret_cast<int*>(sort_buf);     // 2048 ints = 8 KB <= nsort * 8 (nsort >= 1024)
+
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int L = seq_lens[b];
+    if (L <= budget) return;
+    const int Lc = L - window;
+    const int k_eff = k < Lc ? k : Lc;
+    const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
+
+    // 1. score key of the k_eff-th best
+    radix_select(Lc, k_eff,
+                 [&](int t, uint32_t* key) { *key = score_key(row[t]); return true; },
+                 hist, scratch, &st);
+    const uint32_t T = st.prefix;
+    const int need_eq = st.need, count_eq = st.count_eq;
+    __syncthreads();
+
+    // 2. position bound among the ties (rare: only when ties straddle the cut)
+    uint32_t pos_bound = 0xffffffffu;                  // take every tie
+    if (count_eq > need_eq) {
+        radix_select(Lc, need_eq,
+                     [&](int t, uint32_t* key) { *key = ~(uint32_t)t; return score_key(row[t]) == T; },
+                     hist, scratch, &st);
+        pos_bound = ~st.prefix;                        // need_eq-th smallest tying position
+        __syncthreads();
+    }
+
+    // 3. compact the survivors (any order), pad, sort descending
+    if (threadIdx.x == 0) n_out = 0;
+    __syncthreads();                                   // also: histogram no longer needed
+    for (int base = 0; base < Lc; base += SEL_THREADS) {
+        const int t = base + threadIdx.x;
+        bool sel = false;
+        uint32_t key = 0;
+        if (t < Lc) {
+            key = score_key(row[t]);
+            sel = key > T || (key == T && (uint32_t)t <= pos_bound);
+        }
+        const uint64_t ballot = __ballot(sel);
+        int wave_base = 0;
+        if (lane_id() == 0 && ballot) wave_base = atomicAdd(&n_out, __popcll(ballot));
+        wave_base = __shfl(wave_base, 0);
+        if (sel) {
+            const int slot = wave_base + mbcnt(ballot);
+            if (slot < nsort) sort_buf[slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
+        }
+    }
+    __syncthreads();
+    for (int i = k_eff + threadIdx.x; i < nsort; i += SEL_THREADS) sort_buf[i] = 0;
+    __syncthreads();
+    for (int size = 2; size <= nsort; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int p = threadIdx.x; p < (nsort >> 1); p += SEL_THREADS) {
+                const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
+                const int hi = lo + stride;
+                const uint64_t a = sort_buf[lo], c = sort_buf[hi];
+                const bool desc = (lo & size) == 0;
+                if ((a < c) == desc) {
+                    sort_buf[lo] = c;
+                    sort_buf[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // 4. rank-major output
+    int32_t* __restrict__ out = rho_head + (int64_t)b * k * H + h;
+    for (int j = threadIdx.x; j < k_eff; j += SEL_THREADS)
+        out[(int64_t)j * H] = (int32_t)~(uint32_t)sort_buf[j];
+}
+
+// ---------------------------------------------------------------- union / rank / window
+//
+// One 1024-thread workgroup per sequence.  Slot s = j*H + h of the rank-major
+// array is head h's rank-j pick; a token's global rank is the smallest slot that
+// names it.  first[t] = that slot (atomicMin, order-independent); a slot is the
+// "first occurrence" of its token iff first[rho[s]] == s; the cut slot s* is the
+// one at which the count of first occurrences reaches K-W; rho's historical part
+// is {t : first[t] <= s*}, emitted in ascending position order, followed by the
+// window {L-W .. L-1}.
+
+__device__ __forceinline__ int ld_relaxed(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// slot s is the first (lowest) slot naming its token
+__device__ __forceinline__ bool is_first(const int32_t* first, const int32_t* rho, int s, int Lc) {
+    const uint32_t tok = (uint32_t)rho[s];
+    return tok < (uint32_t)Lc && ld_relaxed(&first[tok]) == s;
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __restrict__ rho_head,
+                                                             const int32_t* __restrict__ seq_lens,
+                                                             int32_t* first_all, int64_t ld_first,
+                                                             int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
+                                                             int H, int k, int budget, int window) {
+    __shared__ int wave_cnt[SEL_WAVES];
+    __shared__ int s_star;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int L = seq_lens[b];
+    int32_t* __restrict__ out = idx + (int64_t)b * budget;
+    if (L <= budget) {
+        for (int t = tid; t < L; t += SEL_THREADS) out[t] = t;
+        if (tid == 0) cnt[b] = L;
+        return;
+    }
+    const int Lc = L - window;
+    const int k_eff = k < Lc ? k : Lc;
+    const int S = k_eff * H;
+    const int n_hist = budget - window;
+    int32_t* first = first_all + (int64_t)b * ld_first;
+    const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
+
+    for (int t = tid; t < Lc; t += SEL_THREADS) first[t] = 0x7fffffff;
+    __threadfence();
+    __syncthreads();
+    for (int s = tid; s < S; s += SEL_THREADS) {
+        const uint32_t tok = (uint32_t)rho[s];
+        if (tok < (uint32_t)Lc) atomicMin(&first[tok], s);     // a pick is always a candidate position
+    }
+    __threadfence();
+    __syncthreads();
+
+    // cut slot: each wave owns a contiguous run of slots, walked 64 at a time
+    const int seg = ((S + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
+    const int s_lo = w * seg, s_hi = (s_lo + seg < S) ? s_lo + seg : S;
+    int mine = 0;
+    for (int s0 = s_lo; s0 < s_hi; s0 += 64) {
+        const int s = s0 + lane;
+        const bool f = s < s_hi && is_first(first, rho, s, Lc);
+        mine += __popcll(__ballot(f));
+    }
+    if (lane == 0) wave_cnt[w] = mine;
+    if (tid == 0) s_star = -1;
+    __syncthreads();
+    int before = 0, total = 0;
+    for (int i = 0; i < SEL_WAVES; ++i) {
+        if (i < w) before += wave_cnt[i];
+        total += wave_cnt[i];
+    }
+    const int n_take = n_hist < total ? n_hist : total;   // == n_hist whenever k >= K-W
+    if (n_take > 0 && before < n_take && n_take <= before + mine) {
+        int run = before;
+        for (int s0 = s_lo; s0 < s_hi; s0 += 64) {
+            const int s = s0 + lane;
+            const bool f = s < s_hi && is_first(first, rho, s, Lc);
+            const uint64_t ballot = __ballot(f);
+            const int c = __popcll(ballot);
+            if (run < n_take && n_take <= run + c) {
+                if (f && run + mbcnt(ballot) + 1 == n_take) s_star = s;
+            }
+            run += c;
+        }
+    }
+    __syncthreads();
+    const int cut = s_star;
+
+    // ascending emission: each wave owns a contiguous run of positions
+    const int pseg = ((Lc + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
+    const int p_lo = w * pseg, p_hi = (p_lo + pseg < Lc) ? p_lo + pseg : Lc;
+    int sel_cnt = 0;
+    for (int t0 = p_lo; t0 < p_hi; t0 += 64) {
+        const int t = t0 + lane;
+        const bool f = t < p_hi && ld_relaxed(&first[t]) <= cut;
+        sel_cnt += __popcll(__ballot(f));
+    }
+    __syncthreads();                                      // wave_cnt reuse
+    if (lane == 0) wave_cnt[w] = sel_cnt;
+    __syncthreads();
+    int off = 0;
+    for (int i = 0; i < w; ++i) off += wave_cnt[i];
+    for (int t0 = p_lo; t0 < p_hi; t0 += 64) {
+        const int t = t0 + lane;
+        const bool f = t < p_hi && ld_relaxed(&first[t]) <= cut;
+        const uint64_t ballot = __ballot(f);
+        if (f && off + mbcnt(ballot) < n_hist) out[off + mbcnt(ballot)] = t;
+        off += __popcll(ballot);
+    }
+    for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
+    if (tid == 0) cnt[b] = n_take + window;
+}
+
+// ---------------------------------------------------------------- attention (split-K flash-decode)
+//
+// grid (n_splits, G, B), 256 threads.  A workgroup owns a contiguous run of the
+// sequence's token list (all tokens, or rho) for one KV head and keeps the GQ
+// query heads of that group in registers (pre-multiplied by sm_scale*log2 e).
+// A 256-byte K or V row is read by 16 lanes with one 16-byte load each; a wave
+// therefore covers 4 rows per load instruction and TI*4 rows per iteration.
+// q.k is finished with a 16-lane DPP butterfly, softmax is the usual running
+// (max, sum) rescale per iteration, and P.V accumulates 8 columns per lane.
+// The four waves are merged through LDS into one partial (m, l, acc[128]) per
+// head, which attn_reduce_kernel combines across splits.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// sum over the 16 lanes of a DPP row; every lane of the row gets the result
+__device__ __forceinline__ float row_sum16(float v) {
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
+    return v;
+}
+
+constexpr int ATTN_THREADS = 256;
+constexpr int ATTN_WAVES = 4;
+
+__host__ __device__ inline int attn_chunk(int n, int n_splits, int wg_tile) {
+    int c = (n + n_splits - 1) / n_splits;
+    return (c + wg_tile - 1) / wg_tile * wg_tile;
+}
+
+template <int GQ, int TI, bool SPARSE, bool PAGED>
+__global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
+    KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
+    float* __restrict__ part_ml, int n_splits, int H) {
+    constexpr int TILE = TI * 4;
+    constexpr int WG_TILE = TILE * ATTN_WAVES;
+    __shared__ float sm_acc[ATTN_WAVES][GQ][D];
+    __shared__ float sm_m[ATTN_WAVES][GQ];
+    __shared__ float sm_l[ATTN_WAVES][GQ];
+
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
+    const int L = kv.seq_lens[b];
+    const int n = SPARSE ? min(cnt[b], budget) : L;
+    const int chunk = attn_chunk(n, n_splits, WG_TILE);
+    const int begin = split * chunk;
+    const int end = (begin + chunk < n) ? begin + chunk : n;
+    const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
+
+    float qr[GQ][8];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        const uint4 w = *reinterpret_cast<const uint4*>(q + ((int64_t)b * H + kvh * GQ + h) * D + c * 8);
+        unpack8(w, qr[h]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qr[h][e] *= scale_log2e;
+    }
+    float m[GQ], l[GQ], acc[GQ][8];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        m[h] = -INFINITY;
+        l[h] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+    }
+
+    for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
+        uint4 kreg[TI], vreg[TI];
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            const int ti = t0 + i * 4 + r;
+            kreg[i] = make_uint4(0, 0, 0, 0);
+            vreg[i] = make_uint4(0, 0, 0, 0);
+            if (ti < end) {
+                int pos = ti;
+                if (SPARSE) pos = min(max(my_idx[ti], 0), L - 1);   // an index outside the sequence is a caller error; never fault on it
+                const int64_t off = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
+                kreg[i] = *reinterpret_cast<const uint4*>(kv.k + off);
+                vreg[i] = *reinterpret_cast<const uint4*>(kv.v + off);
+            }
+        }
+        float s[TI][GQ];
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            float kf[8];
+            unpack8(kreg[i], kf);
+            const bool valid = t0 + i * 4 + r < end;
+#pragma unroll
+            for (int h = 0; h < GQ; ++h) {
+                float p = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p = __builtin_fmaf(qr[h][e], kf[e], p);
+                p = row_sum16(p);
+                s[i][h] = valid ? p : -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            float mt = s[0][h];
+#pragma unroll
+            for (int i = 1; i < TI; ++i) mt = fmaxf(mt, s[i][h]);
+            mt = fmaxf(mt, __shfl_xor(mt, 16));
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float m_new = fmaxf(m[h], mt);      // finite: token t0 of this tile is valid
+            const float corr = exp2f(m[h] - m_new);
+            l[h] *= corr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+            m[h] = m_new;
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+                const float p = exp2f(s[i][h] - m_new);
+                l[h] += p;
+                s[i][h] = p;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            float vf[8];
+            unpack8(vreg[i], vf);
+#pragma unroll
+            for (int h = 0; h < GQ; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(s[i][h], vf[e], acc[h][e]);
+        }
+    }
+
+    // merge the wave's four row groups, then the four waves
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        l[h] += __shfl_xor(l[h], 16);
+        l[h] += __shfl_xor(l[h], 32);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            acc[h][e] += __shfl_xor(acc[h][e], 16);
+            acc[h][e] += __shfl_xor(acc[h][e], 32);
+        }
+        if (r == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm_acc[wave][h][c * 8 + e] = acc[h][e];
+        }
+        if (lane == 0) {
+            sm_m[wave][h] = m[h];
+            sm_l[wave][h] = l[h];
+        }
+    }
+    __syncthreads();
+    for (int o = tid; o < GQ * D; o += ATTN_THREADS) {
+        const int h = o / D, col = o % D;
+        float M = sm_m[0][h];
+#pragma unroll
+        for (int wv = 1; wv < ATTN_WAVES; ++wv) M = fmaxf(M, sm_m[wv][h]);
+        float A = 0.0f, Ls = 0.0f;
+#pragma unroll
+        for (int wv = 0; wv < ATTN_WAVES; ++wv) {
+            const float mw = sm_m[wv][h];
+            const float f = (mw == -INFINITY) ? 0.0f : exp2f(mw - M);
+            A = __builtin_fmaf(sm_acc[wv][h][col], f, A);
+            Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
+        }
+        const int64_t p = ((int64_t)b * H + kvh * GQ + h) * n_splits + split;
+        part_acc[p * D + col] = A;
+        if (col == 0) {
+            part_ml[p * 2] = M;
+            part_ml[p * 2 + 1] = Ls;
+        }
+    }
+}
+
+// grid (H, B), 128 threads: thread = output column.
+__global__ __launch_bounds__(D) void attn_reduce_kernel(const float* __restrict__ part_acc,
+                                                         const float* __restrict__ part_ml,
+                                                         uint16_t* __restrict__ out, int n_splits, int H) {
+    const int h = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
+    const int64_t base = ((int64_t)b * H + h) * n_splits;
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
+    float A = 0.0f, Ls = 0.0f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float ms = part_ml[(base + s) * 2];
+        const float f = (ms == -INFINITY) ? 0.0f : exp2f(ms - M);
+        A = __builtin_fmaf(part_acc[(base + s) * D + col], f, A);
+        Ls = __builtin_fmaf(part_ml[(base + s) * 2 + 1], f, Ls);
+    }
+    const float o = Ls > 0.0f ? A / Ls : 0.0f;
+    out[((int64_t)b * H + h) * D + col] = f32_to_bf16_rne(o);
+}
+
+}  // namespace cusa

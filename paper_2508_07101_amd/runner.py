@@ -1,0 +1,73 @@
+"""Glue between a drawn workload and the C-ABI calls: allocates outputs, index
+buffers and workspace with torch and marshals the per-layer descriptors.  No
+arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from . import binding as cb
+from .workloads import Inputs
+
+
+def params_of(inp: Inputs) -> cb.CusaParams:
+    w = inp.workload
+    return cb.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.budget, w.window, w.topk_per_head,
+                          head_dim=w.head_dim)
+
+
+def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:
+    lay = inp.layers[layer_pos]
+    return cb.KvCache(lay.k, lay.v, inp.seq_lens, max(inp.seq_lens_host), inp.block_table)
+
+
+class StepRunner:
+    """One decode step (attention part of Alg. 1) over ``inp.layers`` with ``schedule``."""
+
+    def __init__(self, inp: Inputs, schedule: Optional[List[int]] = None):
+        w = inp.workload
+        self.inp = inp
+        self.schedule = list(w.schedule if schedule is None else schedule)
+        assert len(self.schedule) == len(inp.layers)
+        dev = inp.seq_lens.device
+        self.params = params_of(inp)
+        self.max_len = max(inp.seq_lens_host)
+        self.kvs = [kv_of(inp, i) for i in range(len(inp.layers))]
+        self.outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+                     for _ in inp.layers]
+        self.idx = torch.full((w.batch, w.budget), -1, dtype=torch.int32, device=dev)
+        self.cnt = torch.zeros((w.batch,), dtype=torch.int32, device=dev)
+        self.ws = cb.alloc_workspace(self.params, self.max_len, dev)
+        self.step = cb.DecodeStep(self.params, self.schedule, [l.q for l in inp.layers], self.kvs, self.outs,
+                                  self.idx, self.cnt, self.ws)
+
+    def run(self):
+        self.step.run()
+
+    # single entry points on one layer (by position in inp.layers)
+    def select(self, layer_pos: int):
+        cb.select(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt, self.ws)
+
+    def sparse(self, layer_pos: int):
+        cb.sparse_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt,
+                       self.outs[layer_pos], self.ws)
+
+    def full(self, layer_pos: int):
+        cb.full_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.ws)
+
+    # selection intermediates, for parity tests
+    def scores(self) -> torch.Tensor:
+        lay = cb.workspace_layout(self.params, self.max_len)
+        w = self.inp.workload
+        n = w.batch * w.n_q_heads * lay.ld_scores
+        flat = self.ws[lay.scores_offset: lay.scores_offset + 4 * n].view(torch.float32)
+        return flat.view(w.batch, w.n_q_heads, lay.ld_scores)
+
+    def rho_head(self) -> torch.Tensor:
+        """[B, k, H] rank-major ranked picks."""
+        lay = cb.workspace_layout(self.params, self.max_len)
+        w = self.inp.workload
+        n = w.batch * lay.k * w.n_q_heads
+        flat = self.ws[lay.rho_head_offset: lay.rho_head_offset + 4 * n].view(torch.int32)
+        return flat.view(w.batch, lay.k, w.n_q_heads)

@@ -54,6 +54,7 @@ class Workload:
     page_size: int = 16
     seed: int = BASE_SEED
     same_layer_sparse: bool = False   # single-layer configs: sparse pass on the selection layer's KV
+    lengths: tuple = ()               # explicit per-sequence lengths (tests); overrides the draw
 
     @property
     def k_eff(self) -> int:
@@ -121,6 +122,9 @@ def _normal_bf16(shape, gen, device, add: Optional[torch.Tensor] = None) -> torc
 
 
 def draw_lengths(w: Workload) -> List[int]:
+    if w.lengths:
+        assert len(w.lengths) == w.batch and max(w.lengths) <= w.seq_len
+        return [int(v) for v in w.lengths]
     if w.min_seq_len <= 0:
         return [w.seq_len] * w.batch
     rng = np.random.default_rng(w.seed)

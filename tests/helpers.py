@@ -37,3 +37,43 @@ def dense_attention_f64(q, K, V, tokens=None, sm_scale=None):
         w = np.exp(w - w.max())
         out[h] = (w / w.sum()) @ Vh
     return out
+
+
+def host_view(inp, layer_pos, b):
+    """Logical (q[H,d], K[G,L,d], V[G,L,d]) bf16 bit patterns of sequence b for the oracle."""
+    import oracle
+    from paper_2508_07101_amd.workloads import bf16_bits
+    lay = inp.layers[layer_pos]
+    L = inp.seq_lens_host[b]
+    q = bf16_bits(lay.q[b])
+    if inp.block_table is None:
+        return q, bf16_bits(lay.k[b, :, :L]), bf16_bits(lay.v[b, :, :L])
+    bt = inp.block_table[b].cpu().numpy()
+    n = (L + inp.workload.page_size - 1) // inp.workload.page_size
+    pages = torch_unique_pages(bt[:n])
+    # copy only this sequence's pages to the host, then let the oracle resolve the table
+    import numpy as np
+    import torch
+    sel = torch.as_tensor(pages, device=lay.k.device, dtype=torch.long)
+    remap = {int(p): i for i, p in enumerate(pages)}
+    bt_local = np.array([remap[int(p)] for p in bt[:n]], dtype=np.int32)
+    kp, vp = bf16_bits(lay.k[sel]), bf16_bits(lay.v[sel])
+    return q, oracle.resolve_paged(kp, bt_local, L), oracle.resolve_paged(vp, bt_local, L)
+
+
+def torch_unique_pages(bt_row):
+    seen, out = set(), []
+    for p in bt_row:
+        if int(p) not in seen:
+            seen.add(int(p))
+            out.append(int(p))
+    return out
+
+
+def assert_close_bf16(got_bits, want_bits, what=""):
+    """|got - want| <= 2e-2 + 1e-2 |want| elementwise on bf16 outputs (the stated tolerance)."""
+    g, w = bits_to_f64(got_bits), bits_to_f64(want_bits)
+    err = np.abs(g - w)
+    tol = 2e-2 + 1e-2 * np.abs(w)
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.4g}"

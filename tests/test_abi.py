@@ -1,0 +1,105 @@
+"""The C-ABI library loads, exports every symbol cusa.h declares, and rejects bad
+arguments on the host (no kernel is launched by anything in this file)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_07101_amd import binding as cb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cusa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cusa_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = cb.load()
+    names = _declared_symbols()
+    assert set(names) == set(cb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_strerror_covers_every_status():
+    seen = {cb.strerror(s) for s in range(5)}
+    assert len(seen) == 5 and "unknown status" not in seen
+    assert cb.strerror(99) == "unknown status"
+
+
+def test_workspace_bytes_grows_with_the_problem():
+    p = cb.make_params(1, 32, 8, 2048, 512)
+    a = cb.workspace_bytes(p, 32768)
+    b = cb.workspace_bytes(p, 65536)
+    assert 0 < a < b and a % 256 == 0
+    lay = cb.workspace_layout(p, 32768)
+    assert lay.k == 1536 and lay.ld_scores >= 32768 - 512 and lay.total_bytes == a
+    assert lay.scores_offset % 256 == 0 and lay.rho_head_offset % 256 == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=30), cb.ERR_INVALID_ARG),              # H % G != 0
+    (dict(head_dim=64), cb.ERR_UNSUPPORTED),
+    (dict(n_q_heads=48, n_kv_heads=8), cb.ERR_UNSUPPORTED),  # g = 6
+    (dict(window=4096), cb.ERR_INVALID_ARG),               # W > K
+    (dict(topk_per_head=100), cb.ERR_INVALID_ARG),         # k < K - W
+    (dict(topk_per_head=10000), cb.ERR_UNSUPPORTED),
+    (dict(n_sink=4), cb.ERR_UNSUPPORTED),
+    (dict(rank_mode=cb.RANK_VOTES), cb.ERR_UNSUPPORTED),
+    (dict(rank_mode=7), cb.ERR_INVALID_ARG),
+    (dict(sm_scale=0.0), cb.ERR_INVALID_ARG),
+    (dict(batch=0), cb.ERR_INVALID_ARG),
+])
+def test_bad_params_are_rejected(kw, status):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, budget=2048, window=512)
+    base.update(kw)
+    p = cb.make_params(**base)
+    n = ctypes.c_size_t(0)
+    assert cb.load().cusa_workspace_bytes(ctypes.byref(p), 4096, ctypes.byref(n)) == status
+
+
+def test_null_and_misshapen_arguments_are_rejected_before_any_launch():
+    lib = cb.load()
+    p = cb.make_params(1, 32, 8, 2048, 512)
+    kv = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 128, None, 0, 0, 0, 0x3000, 4096)
+    fake = ctypes.c_void_p(0x10000)
+    # NULL q
+    assert lib.cusa_full_attn(ctypes.byref(p), None, ctypes.byref(kv), fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    # workspace too small / NULL / misaligned
+    assert lib.cusa_full_attn(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    assert lib.cusa_full_attn(ctypes.byref(p), fake, ctypes.byref(kv), fake, None, 1 << 30, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_full_attn(ctypes.byref(p), fake, ctypes.byref(kv), fake, ctypes.c_void_p(0x10010), 1 << 30, None) == cb.ERR_INVALID_ARG
+    # token stride below the row length
+    bad = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 64, None, 0, 0, 0, 0x3000, 4096)
+    assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    # paged: wrong page size, missing table, table too short for max_seq_len
+    pg = cb.CusaKv(0x1000, 0x2000, cb.KV_PAGED, 0, 0, 0, 0x4000, 256, 32, 100, 0x3000, 4096)
+    assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(pg), fake, fake, fake, 1 << 30, None) == cb.ERR_UNSUPPORTED
+    pg = cb.CusaKv(0x1000, 0x2000, cb.KV_PAGED, 0, 0, 0, None, 256, 16, 100, 0x3000, 4096)
+    assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(pg), fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    pg = cb.CusaKv(0x1000, 0x2000, cb.KV_PAGED, 0, 0, 0, 0x4000, 10, 16, 100, 0x3000, 4096)
+    assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(pg), fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    # unknown layout, missing seq_lens
+    bad = cb.CusaKv(0x1000, 0x2000, 5, 0, 4096 * 128, 128, None, 0, 0, 0, 0x3000, 4096)
+    assert lib.cusa_sparse_attn(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    bad = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 128, None, 0, 0, 0, None, 4096)
+    assert lib.cusa_sparse_attn(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+
+
+def test_decode_step_rejects_sparse_before_select_and_unknown_kinds():
+    lib = cb.load()
+    p = cb.make_params(1, 32, 8, 2048, 512)
+    n = 2
+    kvs = (cb.CusaKv * n)(*[cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 128, None, 0, 0, 0, 0x3000, 4096)] * n)
+    ptrs = (ctypes.c_void_p * n)(0x10000, 0x20000)
+    fake = ctypes.c_void_p(0x10000)
+    for kinds in ([cb.LAYER_SPARSE, cb.LAYER_SELECT], [cb.LAYER_FULL, cb.LAYER_SPARSE], [cb.LAYER_FULL, 9]):
+        arr = (ctypes.c_int32 * n)(*kinds)
+        assert lib.cusa_decode_step(ctypes.byref(p), n, arr, ptrs, kvs, ptrs, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    arr = (ctypes.c_int32 * n)(cb.LAYER_SELECT, cb.LAYER_SPARSE)
+    assert lib.cusa_decode_step(ctypes.byref(p), n, arr, ptrs, kvs, ptrs, fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    assert lib.cusa_decode_step(ctypes.byref(p), 0, arr, ptrs, kvs, ptrs, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG

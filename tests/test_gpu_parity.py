@@ -1,0 +1,273 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: selection scores, ranked per-head lists, idx and cnt bit-exact; attention outputs within
+|gpu - oracle| <= 2e-2 + 1e-2 |oracle| on the bf16 values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import assert_close_bf16, host_view
+from paper_2508_07101_amd import workloads as wl
+from paper_2508_07101_amd.runner import StepRunner
+from paper_2508_07101_amd.workloads import LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, bf16_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print(f"[parity] {msg}", flush=True)
+
+
+def small(name="t", **kw):
+    base = dict(name=name, n_layers=2, batch=2, n_q_heads=32, n_kv_heads=8, head_dim=128, seq_len=1500,
+                budget=256, window=64, topk_per_head=0, schedule=(LAYER_SELECT, LAYER_SPARSE), seed=777)
+    base.update(kw)
+    return wl.Workload(**base)
+
+
+def check_select(inp, runner, layer_pos, seqs=None, check_scores=True):
+    w = inp.workload
+    torch.cuda.synchronize()
+    idx = runner.idx.cpu().numpy()
+    cnt = runner.cnt.cpu().numpy()
+    P_dev, rho_dev = runner.scores(), runner.rho_head()
+    for b in (range(w.batch) if seqs is None else seqs):
+        q, K, _ = host_view(inp, layer_pos, b)
+        L = inp.seq_lens_host[b]
+        rho, rho_head, P = oracle.select(q, K, w.budget, w.window, w.topk_per_head, return_all=True)
+        if L > w.budget:
+            Lc = L - w.window
+            if check_scores:
+                got = P_dev[b, :, :Lc].cpu().numpy()
+                assert (got.view(np.uint32) == P.view(np.uint32)).all(), f"scores differ, seq {b}"
+            k_eff = rho_head.shape[1]
+            got = rho_dev[b, :k_eff, :].cpu().numpy().T
+            assert (got == rho_head).all(), f"ranked per-head lists differ, seq {b}: {(got != rho_head).sum()} entries"
+        assert cnt[b] == len(rho) == min(w.budget, L), f"cnt seq {b}: {cnt[b]} vs {len(rho)}"
+        assert (idx[b, : cnt[b]] == rho).all(), f"idx differs, seq {b}"
+
+
+def check_attention(inp, runner, layer_pos, kind, seqs=None):
+    w = inp.workload
+    torch.cuda.synchronize()
+    out = bf16_bits(runner.outs[layer_pos])
+    idx = runner.idx.cpu().numpy()
+    cnt = runner.cnt.cpu().numpy()
+    for b in (range(w.batch) if seqs is None else seqs):
+        q, K, V = host_view(inp, layer_pos, b)
+        rho = idx[b, : cnt[b]] if kind == LAYER_SPARSE else None
+        want = oracle.attention(q, K, V, rho)
+        assert_close_bf16(out[b], want, f"layer {layer_pos} kind {kind} seq {b}")
+
+
+def run_and_check(w, layers=None, seqs=None, check_scores=True):
+    inp = wl.make_inputs(w, DEV, layers)
+    sched = list(w.schedule) if layers is None else [w.schedule[i] for i in layers]
+    r = StepRunner(inp, sched)
+    _say(f"{w.name}: decode step over {len(sched)} layers, lens {inp.seq_lens_host[:6]}...")
+    r.run()
+    torch.cuda.synchronize()
+    sel = max(i for i, k in enumerate(sched) if k == LAYER_SELECT)
+    check_select(inp, r, sel, seqs, check_scores)
+    return inp, r, sched
+
+
+# ------------------------------------------------------------------ small shapes
+
+@pytest.mark.parametrize("H,G", [(8, 8), (16, 8), (32, 8), (64, 8)])
+def test_small_contiguous_all_group_sizes(H, G):
+    w = small(f"g{H // G}", n_q_heads=H, n_kv_heads=G, batch=3, seq_len=1500, min_seq_len=900, n_planted=5)
+    inp, r, sched = run_and_check(w)
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+
+
+def test_small_paged_ragged_with_short_sequences():
+    # lengths from below the budget (rho = everything) to several score tiles with a ragged tail
+    w = small("paged", batch=6, seq_len=2100, lengths=(100, 2100, 256, 257, 1033, 777), paged=True,
+              budget=256, window=64)
+    inp, r, sched = run_and_check(w)
+    assert min(inp.seq_lens_host) <= w.budget < max(inp.seq_lens_host)
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+
+
+def test_lowrank_correlated_heads_and_wider_topk():
+    w = small("lowrank", batch=2, seq_len=3000, lowrank=8, budget=512, window=128, topk_per_head=512)
+    inp, r, sched = run_and_check(w)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+
+
+def test_four_layer_schedule_full_full_select_sparse():
+    w = small("sched", n_layers=5, schedule=(LAYER_FULL, LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SPARSE),
+              batch=2, seq_len=1200)
+    inp, r, sched = run_and_check(w)
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+
+
+@pytest.mark.parametrize("L,K,W,k", [
+    (300, 256, 64, 0),      # L just above K
+    (257, 256, 64, 0),      # L = K + 1
+    (256, 256, 64, 0),      # L = K: everything
+    (5, 256, 64, 0),        # tiny
+    (1, 256, 64, 0),        # the current token only
+    (330, 256, 64, 300),    # Lc = 266 < k: k clamps to Lc
+    (1000, 128, 0, 0),      # no window
+    (1000, 128, 128, 0),    # window only
+    (1000, 64, 16, 1024),   # k far above K - W
+])
+def test_edge_lengths_and_budgets(L, K, W, k):
+    w = small(f"edge{L}_{K}_{W}_{k}", batch=2, seq_len=L, budget=K, window=W, topk_per_head=k)
+    inp, r, sched = run_and_check(w)
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+
+
+def _with_keys(w, fn):
+    inp = wl.make_inputs(w, DEV)
+    fn(inp.layers[0].k)
+    r = StepRunner(inp)
+    r.run()
+    check_select(inp, r, 0)
+    return inp, r
+
+
+def test_ties_duplicated_keys_go_to_lowest_position():
+    w = small("dup", batch=2, seq_len=1400, budget=256, window=64)
+
+    def dup(k):
+        k[:, :, 500:1000] = k[:, :, 0:500]      # every score in [0,500) appears again 500 later
+    _with_keys(w, dup)
+
+
+def test_ties_all_keys_equal():
+    w = small("alleq", batch=1, seq_len=2500, budget=256, window=64)
+
+    def alleq(k):
+        k[:] = k[:, :, :1].clone()               # every candidate ties: ranks are positions 0,1,2,...
+    inp, r = _with_keys(w, alleq)
+    torch.cuda.synchronize()
+    rho = r.rho_head()[0].cpu().numpy()          # [k, H]
+    assert (rho == np.arange(rho.shape[0])[:, None]).all()
+
+
+def test_ties_quantised_keys():
+    w = small("quant", batch=2, seq_len=3000, budget=512, window=128)
+
+    def quant(k):
+        k.copy_(torch.sign(k) * (k.abs() > 0.8))   # keys in {-1, 0, 1}: scores collide heavily
+    _with_keys(w, quant)
+
+
+def test_selection_is_deterministic_across_runs():
+    w = small("det", batch=2, seq_len=4000, budget=512, window=128)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    ref = None
+    for _ in range(3):
+        r.idx.fill_(-1)
+        r.select(0)
+        torch.cuda.synchronize()
+        cur = (r.idx.clone(), r.rho_head().clone())
+        if ref is not None:
+            assert torch.equal(cur[0], ref[0]) and torch.equal(cur[1], ref[1])
+        ref = cur
+
+
+def test_separate_entry_points_match_the_decode_step():
+    w = small("entry", batch=2, seq_len=1700, n_planted=4)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.run()
+    torch.cuda.synchronize()
+    idx, outs = r.idx.clone(), [o.clone() for o in r.outs]
+    r.idx.fill_(-1)
+    r.select(0)
+    r.full(0)
+    r.sparse(1)
+    torch.cuda.synchronize()
+    assert torch.equal(r.idx, idx)
+    assert torch.equal(r.outs[0], outs[0]) and torch.equal(r.outs[1], outs[1])
+
+
+def test_strided_contiguous_cache_view():
+    """K/V given as [B, L, G, d] storage viewed as [B, G, L, d] (token stride G*d)."""
+    w = small("strided", batch=2, seq_len=900)
+    inp = wl.make_inputs(w, DEV)
+    for lay in inp.layers:
+        lay.k = lay.k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        lay.v = lay.v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    r = StepRunner(inp)
+    r.run()
+    check_select(inp, r, 0)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+    check_attention(inp, r, 0, LAYER_FULL)
+
+
+def test_planted_heavy_keys_are_selected_on_gpu():
+    w = small("planted", batch=2, seq_len=4096, budget=256, window=64, n_planted=16)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.run()
+    torch.cuda.synchronize()
+    idx = r.idx.cpu().numpy()
+    planted = inp.layers[0].planted.numpy()
+    for b in range(w.batch):
+        assert set(planted[b]) <= set(idx[b])
+
+
+# ------------------------------------------------------------------ the five workloads at full size
+
+def test_c1_full_size():
+    inp, r, sched = run_and_check(wl.WORKLOADS["c1"])
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+    planted = inp.layers[0].planted.numpy()
+    assert set(planted[0]) <= set(r.idx.cpu().numpy()[0])
+
+
+def test_c2_full_size_whole_step_sampled_layers():
+    w = wl.WORKLOADS["c2"]
+    inp, r, sched = run_and_check(w)
+    for i in (0, 2, 3, 17, 31):
+        _say(f"c2: oracle attention for layer {i}")
+        check_attention(inp, r, i, sched[i])
+
+
+def test_c3_full_size_layer_subset_sampled_sequences():
+    w = wl.WORKLOADS["c3"]
+    layers = [0, 2, 3]
+    inp, r, sched = run_and_check(w, layers, seqs=[0, 5])
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind, seqs=[5])
+
+
+def test_c4_full_size():
+    inp, r, sched = run_and_check(wl.WORKLOADS["c4"])
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind)
+
+
+def test_c5_full_size_layer_subset_sampled_sequences():
+    w = wl.WORKLOADS["c5"]
+    inp = wl.make_inputs(w, DEV, layers=[0, 1])
+    lens = inp.seq_lens_host
+    seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 17})
+    r = StepRunner(inp, [LAYER_SELECT, LAYER_SPARSE])
+    _say(f"c5: 2 layers, sampled sequences {seqs}")
+    r.run()
+    check_select(inp, r, 0, seqs)
+    check_attention(inp, r, 0, LAYER_FULL, seqs[:1])
+    check_attention(inp, r, 1, LAYER_SPARSE, seqs)
+    # properties that hold for every sequence, checked without the oracle
+    torch.cuda.synchronize()
+    idx, cnt = r.idx.cpu().numpy(), r.cnt.cpu().numpy()
+    for b in range(w.batch):
+        assert cnt[b] == w.budget
+        row = idx[b]
+        assert (np.diff(row) > 0).all() and row[0] >= 0
+        assert (row[-w.window:] == np.arange(lens[b] - w.window, lens[b])).all()

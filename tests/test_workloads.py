@@ -1,0 +1,75 @@
+"""The seeded generators: shapes, determinism, planted structure, paged tables (CPU)."""
+import numpy as np
+import torch
+
+import oracle
+from helpers import host_view
+from paper_2508_07101_amd import workloads as wl
+
+
+def _tiny(**kw):
+    base = dict(name="tiny", n_layers=2, batch=3, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=200,
+                budget=32, window=8, topk_per_head=0, schedule=(1, 2), seed=5)
+    base.update(kw)
+    return wl.Workload(**base)
+
+
+def test_five_workloads_have_the_stated_shapes():
+    c = wl.WORKLOADS
+    assert [c[n].n_layers for n in ("c2", "c3", "c5")] == [32, 36, 4]
+    assert c["c2"].schedule[:3] == (0, 0, 1) and set(c["c2"].schedule[3:]) == {2} and len(c["c2"].schedule) == 32
+    assert c["c3"].schedule.count(2) == 33 and c["c5"].schedule == (1, 2, 2, 2)
+    assert (c["c1"].k_eff, c["c2"].k_eff, c["c4"].k_eff) == (1024, 1536, 3072)
+    assert c["c4"].n_q_heads // c["c4"].n_kv_heads == 8 and c["c5"].paged and c["c5"].page_size == 16
+    lens = wl.draw_lengths(c["c5"])
+    assert len(lens) == 64 and min(lens) >= 8192 and max(lens) <= 32768 and lens == wl.draw_lengths(c["c5"])
+
+
+def test_draws_are_seeded_and_free_of_tiny_values():
+    a = wl.make_inputs(_tiny(), "cpu")
+    b = wl.make_inputs(_tiny(), "cpu")
+    for la, lb in zip(a.layers, b.layers):
+        assert torch.equal(la.k, lb.k) and torch.equal(la.q, lb.q) and torch.equal(la.v, lb.v)
+    c = wl.make_inputs(_tiny(seed=6), "cpu")
+    assert not torch.equal(a.layers[0].k, c.layers[0].k)
+    k = a.layers[0].k.float()
+    assert ((k == 0) | (k.abs() >= 2.0 ** -30)).all()
+    assert abs(float(k.std()) - 1.0) < 0.05
+
+
+def test_planted_keys_rank_first_for_every_head():
+    w = _tiny(n_planted=4, seq_len=400)
+    inp = wl.make_inputs(w, "cpu")
+    for b in range(w.batch):
+        q, K, _ = host_view(inp, 0, b)
+        P = oracle.scores(q, K, w.seq_len - w.window)
+        top = oracle.topk(P, 4)
+        planted = set(inp.layers[0].planted[b].tolist())
+        assert max(planted) < w.seq_len - w.window
+        for h in range(w.n_q_heads):
+            assert set(top[h]) == planted
+
+
+def test_paged_pool_and_block_table():
+    w = _tiny(paged=True, lengths=(200, 17, 96))
+    inp = wl.make_inputs(w, "cpu")
+    pages = [(n + 15) // 16 for n in w.lengths]
+    assert inp.n_pages == sum(pages) and inp.layers[0].k.shape == (sum(pages), 2, 16, 128)
+    used = np.concatenate([inp.block_table[b, :n].numpy() for b, n in enumerate(pages)])
+    assert sorted(used.tolist()) == list(range(sum(pages)))          # a permutation of all pool pages
+    assert not (np.diff(used) == 1).all()                             # shuffled
+    q, K, V = host_view(inp, 0, 2)
+    pool = wl.bf16_bits(inp.layers[0].k)
+    for t in (0, 15, 16, 95):
+        page = int(inp.block_table[2, t // 16])
+        np.testing.assert_array_equal(K[1, t], pool[page, 1, t % 16])
+
+
+def test_lowrank_component_correlates_heads():
+    w = _tiny(lowrank=8, lowrank_scale=2.0, seq_len=600, n_q_heads=8, n_kv_heads=8)
+    inp = wl.make_inputs(w, "cpu")
+    q, K, _ = host_view(inp, 0, 0)
+    P = oracle.scores(q, K, 600).astype(np.float64)
+    c = np.corrcoef(P)
+    off = c[~np.eye(8, dtype=bool)]
+    assert off.mean() > 0.2                                           # independent heads would give ~0
