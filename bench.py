@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
@@ -53,8 +55,8 @@ def kernel_bytes(w, lens, acc):
     """Algorithmic bytes of ONE launch of each bandwidth-bound kernel (all sequences of the batch)."""
     G, K, W = w.n_kv_heads, w.budget, w.window
     return {
-        "attn_partial_kernel<full>": sum(acc.full_attn_bytes(G, L) for L in lens),
-        "attn_partial_kernel<sparse>": sum(acc.sparse_attn_bytes(G, K, L) for L in lens),
+        "attn_kernel<full>": sum(acc.full_attn_bytes(G, L) for L in lens),
+        "attn_kernel<sparse>": sum(acc.sparse_attn_bytes(G, K, L) for L in lens),
         "score_kernel": sum(acc.score_bytes(G, L, K, W) for L in lens),
     }
 
@@ -111,7 +113,15 @@ def main():
     r = StepRunner(inp, sched)
     torch.cuda.synchronize()
 
-    step_s = time_steps(r.run, args.steps, args.warmup, torch)
+    run_step = r.run
+    if args.graph:
+        r.run()                                   # warm the library before capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            r.run()
+        run_step = graph.replay
+    step_s = time_steps(run_step, args.steps, args.warmup, torch)
 
     full_s = None
     if not args.no_full_baseline:
@@ -154,7 +164,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads}q/{w.n_kv_heads}kv heads, "
                                f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
                                f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
-                   "schedule": "".join("FSs"[k] for k in sched)},
+                   "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream"},
         "step_algorithmic_bytes": sb["total"],
         "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
         "roofline": roofline,

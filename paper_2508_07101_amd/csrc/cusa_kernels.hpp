@@ -8,9 +8,9 @@
 //                       order-preserving keys, then a bitonic sort in LDS
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
 //                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
-//   attn_partial_kernel split-K flash-decode over all tokens or over rho
-//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers
-//   attn_reduce_kernel  merges the split-K partials and writes bf16
+//   attn_kernel         split-K flash-decode over all tokens or over rho
+//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers;
+//                       the last workgroup to finish merges the splits
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -463,7 +463,9 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 // q.k is finished with a 16-lane DPP butterfly, softmax is the usual running
 // (max, sum) rescale per iteration, and P.V accumulates 8 columns per lane.
 // The four waves are merged through LDS into one partial (m, l, acc[128]) per
-// head, which attn_reduce_kernel combines across splits.
+// head.  With one split that is the result; otherwise the partial goes to the
+// workspace, the workgroup takes a ticket, and whichever workgroup of the
+// (sequence, KV head) arrives last merges all splits and writes bf16.
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
@@ -479,6 +481,27 @@ __device__ __forceinline__ float row_sum16(float v) {
     return v;
 }
 
+// device-coherent accesses for data handed from one workgroup to another inside a kernel
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+#ifdef CUSA_TRACE
+__device__ unsigned long long g_trace[8192 * 8];
+#define CUSA_TRACE_POINT(slot)                                                                         \
+    do {                                                                                               \
+        if (threadIdx.x == 0) {                                                                        \
+            int wg_ = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);                  \
+            if (wg_ < 8192) g_trace[wg_ * 8 + (slot)] = wall_clock64();                                \
+        }                                                                                              \
+    } while (0)
+#else
+#define CUSA_TRACE_POINT(slot) do {} while (0)
+#endif
+
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_WAVES = 4;
 
@@ -488,16 +511,18 @@ __host__ __device__ inline int attn_chunk(int n, int n_splits, int wg_tile) {
 }
 
 template <int GQ, int TI, bool SPARSE, bool PAGED>
-__global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
+__global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
-    float* __restrict__ part_ml, int n_splits, int H) {
+    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* part_acc, float* part_ml,
+    int32_t* counters, uint16_t* __restrict__ out, int n_splits, int H) {
     constexpr int TILE = TI * 4;
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     __shared__ float sm_acc[ATTN_WAVES][GQ][D];
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
+    __shared__ int s_last;
 
+    CUSA_TRACE_POINT(0);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
     const int L = kv.seq_lens[b];
@@ -525,20 +550,28 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
     }
 
     for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
+        // Rows past the end of the run are clamped to its last token (a valid row) so that all
+        // loads are unconditional and issue back to back; their scores are masked below.
         uint4 kreg[TI], vreg[TI];
+        int pos[TI];
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
-            const int ti = t0 + i * 4 + r;
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            vreg[i] = make_uint4(0, 0, 0, 0);
-            if (ti < end) {
-                int pos = ti;
-                if (SPARSE) pos = min(max(my_idx[ti], 0), L - 1);   // an index outside the sequence is a caller error; never fault on it
-                const int64_t off = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
-                kreg[i] = *reinterpret_cast<const uint4*>(kv.k + off);
-                vreg[i] = *reinterpret_cast<const uint4*>(kv.v + off);
-            }
+            const int ti = min(t0 + i * 4 + r, end - 1);
+            pos[i] = SPARSE ? my_idx[ti] : ti;
         }
+        if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // all index loads first
+        int64_t off[TI];
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            if (SPARSE) pos[i] = min(max(pos[i], 0), L - 1);   // an index outside the sequence is a caller error; never fault on it
+            off[i] = row_offset<PAGED>(kv, b, kvh, pos[i]) + c * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            kreg[i] = *reinterpret_cast<const uint4*>(kv.k + off[i]);
+            vreg[i] = *reinterpret_cast<const uint4*>(kv.v + off[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         float s[TI][GQ];
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
@@ -585,6 +618,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
         }
     }
 
+    CUSA_TRACE_POINT(1);
     // merge the wave's four row groups, then the four waves
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
@@ -605,6 +639,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
         }
     }
     __syncthreads();
+    const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
     for (int o = tid; o < GQ * D; o += ATTN_THREADS) {
         const int h = o / D, col = o % D;
         float M = sm_m[0][h];
@@ -618,32 +653,112 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_partial_kernel(
             A = __builtin_fmaf(sm_acc[wv][h][col], f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
-        const int64_t p = ((int64_t)b * H + kvh * GQ + h) * n_splits + split;
-        part_acc[p * D + col] = A;
-        if (col == 0) {
-            part_ml[p * 2] = M;
-            part_ml[p * 2 + 1] = Ls;
+        if (n_splits == 1) {                             // this workgroup saw the whole token list
+            out[(head0 + h) * D + col] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
+        } else {
+            const int64_t p = (head0 + h) * n_splits + split;
+            st_agent(&part_acc[p * D + col], A);
+            if (col == 0) {
+                st_agent(&part_ml[p * 2], M);
+                st_agent(&part_ml[p * 2 + 1], Ls);
+            }
         }
     }
+    if (n_splits == 1) return;
+    CUSA_TRACE_POINT(2);
+
+    // The workgroup that arrives last for this (sequence, KV head) merges all splits.
+    // Partials travel through device-coherent (write-through / cache-bypassing) accesses,
+    // so no whole-cache write-back is needed: the barrier below waits until this
+    // workgroup's stores have completed, and only then is the ticket taken.
+    __syncthreads();
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(&counters[b * gridDim.y + kvh], 1, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (old == n_splits - 1);
+    }
+    __syncthreads();
+    CUSA_TRACE_POINT(3);
+    if (!s_last) return;
+
+    // Thread (col, half) folds the splits s = half, half+2, ... of every head into a running
+    // (m, l, a); loads are issued U splits x GQ heads at a time so that many are in flight.
+    constexpr int U = GQ >= 8 ? 4 : 8;
+    const int col = tid & (D - 1), half = tid >> 7;
+    const int64_t base = head0 * n_splits;               // partial (h, s) lives at base + h*n_splits + s
+    float mo[GQ], lo[GQ], ao[GQ];
+#pragma unroll
+    for (int h = 0; h < GQ; ++h) {
+        mo[h] = -INFINITY;
+        lo[h] = 0.0f;
+        ao[h] = 0.0f;
+    }
+    for (int s0 = half; s0 < n_splits; s0 += 2 * U) {
+        float va[GQ][U];
+        uint64_t vml[GQ][U];
+#pragma unroll
+        for (int h = 0; h < GQ; ++h)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int sv = s0 + 2 * u;
+                const int64_t p = base + h * n_splits + (sv < n_splits ? sv : s0);
+                va[h][u] = ld_agent(&part_acc[p * D + col]);
+                vml[h][u] = __hip_atomic_load(reinterpret_cast<const uint64_t*>(&part_ml[p * 2]), __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            float mb = mo[h];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (s0 + 2 * u < n_splits) mb = fmaxf(mb, __uint_as_float((uint32_t)vml[h][u]));
+            if (mb == -INFINITY) continue;               // nothing but empty splits so far
+            const float f0 = (mo[h] == -INFINITY) ? 0.0f : exp2f(mo[h] - mb);
+            ao[h] *= f0;
+            lo[h] *= f0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float mu = __uint_as_float((uint32_t)vml[h][u]);
+                const float lu = __uint_as_float((uint32_t)(vml[h][u] >> 32));
+                const float f = (s0 + 2 * u < n_splits && mu != -INFINITY) ? exp2f(mu - mb) : 0.0f;
+                ao[h] = __builtin_fmaf(va[h][u], f, ao[h]);
+                lo[h] = __builtin_fmaf(lu, f, lo[h]);
+            }
+            mo[h] = mb;
+        }
+    }
+    float* red = &sm_acc[0][0][0];                       // [3][GQ][128]: the odd half's (m, l, a)
+    if (half == 1) {
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            red[(0 * GQ + h) * D + col] = mo[h];
+            red[(1 * GQ + h) * D + col] = lo[h];
+            red[(2 * GQ + h) * D + col] = ao[h];
+        }
+    }
+    __syncthreads();
+    if (half == 0) {
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) {
+            const float m1 = red[(0 * GQ + h) * D + col], l1 = red[(1 * GQ + h) * D + col];
+            const float a1 = red[(2 * GQ + h) * D + col];
+            const float mb = fmaxf(mo[h], m1);
+            const float f0 = (mo[h] == -INFINITY) ? 0.0f : exp2f(mo[h] - mb);
+            const float f1 = (m1 == -INFINITY) ? 0.0f : exp2f(m1 - mb);
+            const float ls = lo[h] * f0 + l1 * f1;
+            const float o = ls > 0.0f ? (ao[h] * f0 + a1 * f1) / ls : 0.0f;
+            out[(head0 + h) * D + col] = f32_to_bf16_rne(o);
+        }
+    }
+    CUSA_TRACE_POINT(4);
+    if (tid == 0)                                        // leave the ticket ready for the next launch
+        __hip_atomic_store(&counters[b * gridDim.y + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// grid (H, B), 128 threads: thread = output column.
-__global__ __launch_bounds__(D) void attn_reduce_kernel(const float* __restrict__ part_acc,
-                                                         const float* __restrict__ part_ml,
-                                                         uint16_t* __restrict__ out, int n_splits, int H) {
-    const int h = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
-    const int64_t base = ((int64_t)b * H + h) * n_splits;
-    float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
-    float A = 0.0f, Ls = 0.0f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float ms = part_ml[(base + s) * 2];
-        const float f = (ms == -INFINITY) ? 0.0f : exp2f(ms - M);
-        A = __builtin_fmaf(part_acc[(base + s) * D + col], f, A);
-        Ls = __builtin_fmaf(part_ml[(base + s) * 2 + 1], f, Ls);
-    }
-    const float o = Ls > 0.0f ? A / Ls : 0.0f;
-    out[((int64_t)b * H + h) * D + col] = f32_to_bf16_rne(o);
+// Clears the split tickets; enqueued once at the start of every library call that runs attention.
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 }  // namespace cusa
