@@ -16,9 +16,9 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_QF32 = 0, KID_SCORE, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_ZERO, KID_COUNT };
+enum KernelId { KID_QF32 = 0, KID_SCORE, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"q_to_f32_kernel", "score_kernel", "topk_kernel", "union_kernel",
-                                             "attn_kernel<full>", "attn_kernel<sparse>", "zero_i32_kernel"};
+                                             "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel"};
 
 struct ProfRec {
     int id;
@@ -155,7 +155,7 @@ AttnPlan plan_attn(int n_max, int BG, int g) {
 }
 
 struct WsLayout {
-    size_t qf, scores, rho_head, first, part_acc, part_ml, counters, total;
+    size_t qf, scores, rho_head, first, part_acc, part_ml, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -180,7 +180,6 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     w.first = off;     off += align256((size_t)(B * w.ldp) * 4);
     w.part_acc = off;  off += align256((size_t)(B * H * w.max_splits * D) * 4);
     w.part_ml = off;   off += align256((size_t)(B * H * w.max_splits * 2) * 4);
-    w.counters = off;  off += align256((size_t)BG * 4);
     w.total = off;
     return w;
 }
@@ -203,24 +202,24 @@ cusa_status launch_status() { return hipGetLastError() == hipSuccess ? CUSA_OK :
 template <int GQ, int TI, bool SPARSE>
 void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                          const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                         int32_t* ctr, uint16_t* out, int n_splits, int H) {
+                         uint16_t* out, int n_splits, int H) {
     if (paged)
-        attn_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, ctr, out, n_splits, H);
+        attn_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
     else
-        attn_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, ctr, out, n_splits, H);
+        attn_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
 }
 
 template <int GQ, bool SPARSE>
 void launch_attn_ti(int ti, bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                     const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                    int32_t* ctr, uint16_t* out, int n_splits, int H) {
+                    uint16_t* out, int n_splits, int H) {
     if constexpr (GQ <= 4) {
         if (ti == 8) {
-            launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, ctr, out, n_splits, H);
+            launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
             return;
         }
     }
-    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, ctr, out, n_splits, H);
+    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
 }
 
 // Attention over all tokens (idx == nullptr) or over idx/cnt; n_max bounds the token count.
@@ -235,28 +234,23 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     const float scale = p->sm_scale * 1.4426950408889634f;
     float* pa = ws_ptr<float>(ws, w.part_acc);
     float* pm = ws_ptr<float>(ws, w.part_ml);
-    int32_t* ctr = ws_ptr<int32_t>(ws, w.counters);
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     uint16_t* oo = static_cast<uint16_t*>(out);
     dim3 grid(pl.n_splits, p->n_kv_heads, p->batch);
     {
         ProfScope ps(SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL, s);
         switch (g) {
-            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, ctr, oo, pl.n_splits, H); break;
-            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, ctr, oo, pl.n_splits, H); break;
-            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, ctr, oo, pl.n_splits, H); break;
-            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, ctr, oo, pl.n_splits, H); break;
+            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
+            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
+            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
+            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
         }
     }
-    return launch_status();
-}
-
-// The split tickets must read zero when an attention kernel starts; each kernel leaves
-// them at zero again, so one clear per library call is enough.
-cusa_status clear_tickets(const cusa_params* p, void* ws, const WsLayout& w, hipStream_t s) {
-    const int n = p->batch * p->n_kv_heads;
-    ProfScope ps(KID_ZERO, s);
-    zero_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(ws_ptr<int32_t>(ws, w.counters), n);
+    if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+    if (pl.n_splits > 1) {
+        ProfScope ps(KID_REDUCE, s);
+        attn_reduce_kernel<<<dim3(H, p->batch), 256, 0, s>>>(pa, pm, oo, pl.n_splits, H);
+    }
     return launch_status();
 }
 
@@ -368,7 +362,6 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
     const WsLayout w = make_layout(params, kv->max_seq_len);
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
-    if ((st = clear_tickets(params, ws, w, static_cast<hipStream_t>(stream))) != CUSA_OK) return st;
     return run_attention<true>(params, q, kv, idx, cnt, n_max, out, ws, w, static_cast<hipStream_t>(stream));
 }
 
@@ -380,7 +373,6 @@ cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_
     if (!q || !out || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
     const WsLayout w = make_layout(params, kv->max_seq_len);
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
-    if ((st = clear_tickets(params, ws, w, static_cast<hipStream_t>(stream))) != CUSA_OK) return st;
     return run_attention<false>(params, q, kv, nullptr, nullptr, kv->max_seq_len, out, ws, w,
                                 static_cast<hipStream_t>(stream));
 }
@@ -410,7 +402,6 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
     const WsLayout w = make_layout(params, max_len);
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if ((st = clear_tickets(params, ws, w, s)) != CUSA_OK) return st;
     for (int i = 0; i < n_layers; ++i) {
         const cusa_kv* kv = &kv_layers[i];
         if (layer_kind[i] == CUSA_LAYER_SPARSE) {

@@ -9,8 +9,8 @@
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
 //                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
 //   attn_kernel         split-K flash-decode over all tokens or over rho
-//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers;
-//                       the last workgroup to finish merges the splits
+//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers
+//   attn_reduce_kernel  merges the split-K partials and writes bf16
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -463,9 +463,10 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 // q.k is finished with a 16-lane DPP butterfly, softmax is the usual running
 // (max, sum) rescale per iteration, and P.V accumulates 8 columns per lane.
 // The four waves are merged through LDS into one partial (m, l, acc[128]) per
-// head.  With one split that is the result; otherwise the partial goes to the
-// workspace, the workgroup takes a ticket, and whichever workgroup of the
-// (sequence, KV head) arrives last merges all splits and writes bf16.
+// head.  With one split that is the result and is written as bf16; otherwise the
+// partial goes to the workspace and attn_reduce_kernel merges the splits.  (A merge
+// inside this kernel by the last workgroup to arrive was measured and is slower: its
+// device-coherent reads of the other workgroups' partials run at a few GB/s.)
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
@@ -481,13 +482,8 @@ __device__ __forceinline__ float row_sum16(float v) {
     return v;
 }
 
-// device-coherent accesses for data handed from one workgroup to another inside a kernel
-__device__ __forceinline__ void st_agent(float* p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 #ifdef CUSA_TRACE
 __device__ unsigned long long g_trace[8192 * 8];
@@ -513,14 +509,13 @@ __host__ __device__ inline int attn_chunk(int n, int n_splits, int wg_tile) {
 template <int GQ, int TI, bool SPARSE, bool PAGED>
 __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* part_acc, float* part_ml,
-    int32_t* counters, uint16_t* __restrict__ out, int n_splits, int H) {
+    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
+    float* __restrict__ part_ml, uint16_t* __restrict__ out, int n_splits, int H) {
     constexpr int TILE = TI * 4;
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     __shared__ float sm_acc[ATTN_WAVES][GQ][D];
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
-    __shared__ int s_last;
 
     CUSA_TRACE_POINT(0);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -657,108 +652,75 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             out[(head0 + h) * D + col] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
         } else {
             const int64_t p = (head0 + h) * n_splits + split;
-            st_agent(&part_acc[p * D + col], A);
+            part_acc[p * D + col] = A;
             if (col == 0) {
-                st_agent(&part_ml[p * 2], M);
-                st_agent(&part_ml[p * 2 + 1], Ls);
+                part_ml[p * 2] = M;
+                part_ml[p * 2 + 1] = Ls;
             }
         }
     }
-    if (n_splits == 1) return;
-    CUSA_TRACE_POINT(2);
-
-    // The workgroup that arrives last for this (sequence, KV head) merges all splits.
-    // Partials travel through device-coherent (write-through / cache-bypassing) accesses,
-    // so no whole-cache write-back is needed: the barrier below waits until this
-    // workgroup's stores have completed, and only then is the ticket taken.
-    __syncthreads();
-    if (tid == 0) {
-        const int old = __hip_atomic_fetch_add(&counters[b * gridDim.y + kvh], 1, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (old == n_splits - 1);
-    }
-    __syncthreads();
-    CUSA_TRACE_POINT(3);
-    if (!s_last) return;
-
-    // Thread (col, half) folds the splits s = half, half+2, ... of every head into a running
-    // (m, l, a); loads are issued U splits x GQ heads at a time so that many are in flight.
-    constexpr int U = GQ >= 8 ? 4 : 8;
-    const int col = tid & (D - 1), half = tid >> 7;
-    const int64_t base = head0 * n_splits;               // partial (h, s) lives at base + h*n_splits + s
-    float mo[GQ], lo[GQ], ao[GQ];
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-        mo[h] = -INFINITY;
-        lo[h] = 0.0f;
-        ao[h] = 0.0f;
-    }
-    for (int s0 = half; s0 < n_splits; s0 += 2 * U) {
-        float va[GQ][U];
-        uint64_t vml[GQ][U];
-#pragma unroll
-        for (int h = 0; h < GQ; ++h)
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int sv = s0 + 2 * u;
-                const int64_t p = base + h * n_splits + (sv < n_splits ? sv : s0);
-                va[h][u] = ld_agent(&part_acc[p * D + col]);
-                vml[h][u] = __hip_atomic_load(reinterpret_cast<const uint64_t*>(&part_ml[p * 2]), __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-            }
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) {
-            float mb = mo[h];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (s0 + 2 * u < n_splits) mb = fmaxf(mb, __uint_as_float((uint32_t)vml[h][u]));
-            if (mb == -INFINITY) continue;               // nothing but empty splits so far
-            const float f0 = (mo[h] == -INFINITY) ? 0.0f : exp2f(mo[h] - mb);
-            ao[h] *= f0;
-            lo[h] *= f0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float mu = __uint_as_float((uint32_t)vml[h][u]);
-                const float lu = __uint_as_float((uint32_t)(vml[h][u] >> 32));
-                const float f = (s0 + 2 * u < n_splits && mu != -INFINITY) ? exp2f(mu - mb) : 0.0f;
-                ao[h] = __builtin_fmaf(va[h][u], f, ao[h]);
-                lo[h] = __builtin_fmaf(lu, f, lo[h]);
-            }
-            mo[h] = mb;
-        }
-    }
-    float* red = &sm_acc[0][0][0];                       // [3][GQ][128]: the odd half's (m, l, a)
-    if (half == 1) {
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) {
-            red[(0 * GQ + h) * D + col] = mo[h];
-            red[(1 * GQ + h) * D + col] = lo[h];
-            red[(2 * GQ + h) * D + col] = ao[h];
-        }
-    }
-    __syncthreads();
-    if (half == 0) {
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) {
-            const float m1 = red[(0 * GQ + h) * D + col], l1 = red[(1 * GQ + h) * D + col];
-            const float a1 = red[(2 * GQ + h) * D + col];
-            const float mb = fmaxf(mo[h], m1);
-            const float f0 = (mo[h] == -INFINITY) ? 0.0f : exp2f(mo[h] - mb);
-            const float f1 = (m1 == -INFINITY) ? 0.0f : exp2f(m1 - mb);
-            const float ls = lo[h] * f0 + l1 * f1;
-            const float o = ls > 0.0f ? (ao[h] * f0 + a1 * f1) / ls : 0.0f;
-            out[(head0 + h) * D + col] = f32_to_bf16_rne(o);
-        }
-    }
-    CUSA_TRACE_POINT(4);
-    if (tid == 0)                                        // leave the ticket ready for the next launch
-        __hip_atomic_store(&counters[b * gridDim.y + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Clears the split tickets; enqueued once at the start of every library call that runs attention.
-__global__ void zero_i32_kernel(int32_t* p, int n) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+// Merge of the split-K partials.  grid (H, B), 256 threads: thread (c4, sr) owns output
+// columns 4*c4 .. 4*c4+3 and folds the splits sr, sr+8, ... into a running (m, l, a[4])
+// with 16-byte loads; the eight split-rows then meet in LDS and the result is written as bf16.
+__global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restrict__ part_acc,
+                                                           const float* __restrict__ part_ml,
+                                                           uint16_t* __restrict__ out, int n_splits, int H) {
+    __shared__ float red_a[8][D];
+    __shared__ float red_m[8], red_l[8];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, c4 = tid & 31, sr = tid >> 5;
+    const int64_t base = ((int64_t)b * H + h) * n_splits;
+    constexpr int U = 4;
+    float mo = -INFINITY, lo = 0.0f;
+    f32x4 ao = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s0 = sr; s0 < n_splits; s0 += 8 * U) {
+        f32x4 va[U];
+        f32x2 vml[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sv = s0 + 8 * u;
+            const int64_t p = base + (sv < n_splits ? sv : s0);
+            va[u] = *reinterpret_cast<const f32x4*>(&part_acc[p * D + c4 * 4]);
+            vml[u] = *reinterpret_cast<const f32x2*>(&part_ml[p * 2]);
+        }
+        float mb = mo;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (s0 + 8 * u < n_splits) mb = fmaxf(mb, vml[u].x);
+        if (mb == -INFINITY) continue;                   // nothing but empty splits so far
+        const float f0 = (mo == -INFINITY) ? 0.0f : exp2f(mo - mb);
+        ao *= f0;
+        lo *= f0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float mu = vml[u].x;
+            const float f = (s0 + 8 * u < n_splits && mu != -INFINITY) ? exp2f(mu - mb) : 0.0f;
+            ao += va[u] * f;
+            lo = __builtin_fmaf(vml[u].y, f, lo);
+        }
+        mo = mb;
+    }
+    *reinterpret_cast<f32x4*>(&red_a[sr][c4 * 4]) = ao;
+    if (c4 == 0) {
+        red_m[sr] = mo;
+        red_l[sr] = lo;
+    }
+    __syncthreads();
+    if (tid < D) {
+        float M = red_m[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) M = fmaxf(M, red_m[j]);
+        float A = 0.0f, Ls = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float mj = red_m[j];
+            const float f = (mj == -INFINITY) ? 0.0f : exp2f(mj - M);
+            A = __builtin_fmaf(red_a[j][tid], f, A);
+            Ls = __builtin_fmaf(red_l[j], f, Ls);
+        }
+        out[((int64_t)b * H + h) * D + tid] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
+    }
 }
 
 }  // namespace cusa
