@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "cusa_kernels.hpp"
@@ -254,6 +255,43 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     return launch_status();
 }
 
+// LDS beyond 48 KB per workgroup has to be granted per kernel; remembered per kernel so the
+// runtime is asked once.
+constexpr size_t UNION_LDS_TABLE_MAX = 144 * 1024;
+
+bool allow_dynamic_lds(const void* fn, size_t bytes) {
+    static std::mutex mu;
+    static std::vector<std::pair<const void*, size_t>> granted;
+    std::lock_guard<std::mutex> lk(mu);
+    for (auto& g : granted)
+        if (g.first == fn && g.second >= bytes) return true;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    granted.emplace_back(fn, bytes);
+    return true;
+}
+
+template <int ITEMS, int MTOP>
+cusa_status launch_topk_m(dim3 grid, size_t shmem, hipStream_t s, const float* P, int64_t ldp,
+                          const int32_t* seq_lens, int32_t* rho_head, int H, int k, int budget, int window,
+                          int nsort) {
+    if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
+        return CUSA_ERR_LAUNCH;
+    topk_kernel<ITEMS, MTOP><<<grid, SEL_THREADS, shmem, s>>>(P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+    return launch_status();
+}
+
+// MTOP: per-thread candidates kept for the lower bound, MTOP * 1024 >= k.
+template <int ITEMS>
+cusa_status launch_topk(dim3 grid, size_t shmem, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
+                        int32_t* rho_head, int H, int k, int budget, int window, int nsort) {
+    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+    return launch_topk_m<ITEMS, 8>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+}
+
 template <int GQ>
 void launch_score(bool paged, dim3 grid, hipStream_t s, const KvView& view, const float* qf, float* P, int64_t ldp,
                   int H, int budget, int window) {
@@ -295,22 +333,31 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         int nsort = 1024;
         while (nsort < w.k) nsort <<= 1;
         const size_t shmem = (size_t)nsort * sizeof(uint64_t);
-        if (shmem > 48 * 1024) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem) != hipSuccess)
-                return CUSA_ERR_LAUNCH;
-        }
+        const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
+        cusa_status st;
         {
             ProfScope ps(KID_TOPK, s);
-            topk_kernel<<<dim3(H, B), SEL_THREADS, shmem, s>>>(P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget,
-                                                               p->window, nsort);
+            const dim3 tg(H, B);
+            if (items <= 4) st = launch_topk<4>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
+            else if (items <= 8) st = launch_topk<8>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
+            else if (items <= 16) st = launch_topk<16>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
+            else if (items <= 32) st = launch_topk<32>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
+            else st = launch_topk<0>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
         }
-        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+        if (st != CUSA_OK) return st;
     }
     {
         ProfScope ps(KID_UNION, s);
-        union_kernel<<<B, SEL_THREADS, 0, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k, p->budget,
-                                               p->window);
+        const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
+        const size_t table = ((size_t)lc_max * 4 + 255) & ~(size_t)255;
+        bool in_lds = lc_max > 0 && table <= UNION_LDS_TABLE_MAX;
+        if (in_lds && table > 48 * 1024) in_lds = allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel<true>), table);
+        if (in_lds)
+            union_kernel<true><<<B, SEL_THREADS, table, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
+                                                             p->budget, p->window);
+        else
+            union_kernel<false><<<B, SEL_THREADS, 0, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
+                                                          p->budget, p->window);
     }
     return launch_status();
 }

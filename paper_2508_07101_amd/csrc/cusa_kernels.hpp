@@ -17,6 +17,21 @@
 
 namespace cusa {
 
+// Development aid: builds with -DCUSA_TRACE record wall-clock stamps per workgroup.
+#ifdef CUSA_TRACE
+__device__ unsigned long long g_trace[8192 * 8];
+#define CUSA_TRACE_POINT(slot)                                                                         \
+    do {                                                                                               \
+        if (threadIdx.x == 0) {                                                                        \
+            int wg_ = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);                  \
+            if (wg_ < 8192) g_trace[wg_ * 8 + (slot)] = wall_clock64();                                \
+        }                                                                                              \
+    } while (0)
+#else
+#define CUSA_TRACE_POINT(slot) do {} while (0)
+#endif
+
+
 constexpr int D = 128;        // head_dim
 constexpr int PAGE = 16;      // tokens per page of a paged cache
 
@@ -190,6 +205,9 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 //      over ~position finds the position bound among the ties;
 //   3. the k survivors are compacted into LDS and bitonic-sorted (descending);
 //   4. ranks are written rank-major: rho_head[b][j][h].
+// With ITEMS > 0 a thread keeps its ITEMS candidates (positions i*1024 + tid) in
+// registers, loaded once with independent loads; ITEMS == 0 re-reads the scores from
+// memory in every pass, eight independent loads at a time (any length).
 
 struct SelectState {
     uint32_t prefix;     // digits fixed so far
@@ -231,12 +249,15 @@ __device__ __forceinline__ void pick_digit(int* hist, int* scratch, SelectState*
     __syncthreads();
 }
 
-// Radix select of the `need`-th largest 32-bit key among the n candidates for
-// which key_of(t, &key) returns true.  Leaves the key in st->prefix, the number
-// still wanted among equal keys in st->need, and their count in st->count_eq.
-template <typename KeyOf>
-__device__ __forceinline__ void radix_select(int n, int need, KeyOf key_of, int* hist, int* scratch,
-                                             SelectState* st) {
+// Radix select of the `need`-th largest 32-bit key among this workgroup's candidates.
+// scan(f) must call f(key, t, valid) for every candidate slot of the calling thread, the
+// same number of times in every lane of a wave.  accept(key, t) narrows the candidates.
+// Leaves the key in st->prefix, the number still wanted among equal keys in st->need and
+// their count in st->count_eq.
+// Keys whose top digit is below min_digit0 are known not to matter and are not counted.
+template <typename Scan, typename KeyMap>
+__device__ __forceinline__ void radix_select(int need, uint32_t min_digit0, Scan scan, KeyMap key_map, int* hist,
+                                             int* scratch, SelectState* st) {
     if (threadIdx.x == 0) {
         st->prefix = 0;
         st->need = need;
@@ -251,10 +272,12 @@ __device__ __forceinline__ void radix_select(int n, int need, KeyOf key_of, int*
         const uint32_t prefix = st->prefix;
         const int shift = shifts[pass];
         const uint32_t dmask = (1u << bits[pass]) - 1u;
-        for (int t = threadIdx.x; t < n; t += SEL_THREADS) {
+        const uint32_t floor_d = pass == 0 ? min_digit0 : 0u;
+        scan([&](uint32_t skey, int t, bool valid) {
             uint32_t key;
-            if (key_of(t, &key) && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & dmask], 1);
-        }
+            if (valid && key_map(skey, t, &key) && (key & mask) == prefix && ((key >> shift) & dmask) >= floor_d)
+                atomicAdd(&hist[(key >> shift) & dmask], 1);
+        });
         __syncthreads();
         if (pass < 2) pick_digit<2048>(hist, scratch, st, shift);
         else pick_digit<1024>(hist, scratch, st, shift);
@@ -262,6 +285,7 @@ __device__ __forceinline__ void radix_select(int n, int need, KeyOf key_of, int*
     }
 }
 
+template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
@@ -279,35 +303,97 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     const int k_eff = k < Lc ? k : Lc;
     const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
 
+    CUSA_TRACE_POINT(0);
+    uint32_t keys[ITEMS > 0 ? ITEMS : 1];
+    if constexpr (ITEMS > 0) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int t = i * SEL_THREADS + threadIdx.x;
+            const uint32_t kv_ = score_key(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
+            keys[i] = t < Lc ? kv_ : 0u;
+        }
+    }
+    auto scan = [&](auto f) {
+        if constexpr (ITEMS > 0) {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                const int t = i * SEL_THREADS + threadIdx.x;
+                f(keys[i], t, t < Lc);
+            }
+        } else {
+            for (int t0 = 0; t0 < Lc; t0 += 8 * SEL_THREADS) {
+                uint32_t kk[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + u * SEL_THREADS + threadIdx.x;
+                    kk[u] = score_key(row[t < Lc ? t : Lc - 1]);          // clamped: loads stay unconditional
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + u * SEL_THREADS + threadIdx.x;
+                    f(kk[u], t, t < Lc);
+                }
+            }
+        }
+    };
+
+    // 0. a cheap lower bound for the k_eff-th best key.  Each thread keeps the MTOP largest of
+    //    its own candidates (MTOP * 1024 >= k); the k_eff-th largest of those values cannot
+    //    exceed the k_eff-th largest of all candidates, so its top digit d0 bounds the answer's
+    //    from below and the first histogram pass may skip every key under d0 -- most of them,
+    //    which matters because LDS histogram atomics are what this kernel is bound by.
+    uint32_t top[MTOP];
+#pragma unroll
+    for (int j = 0; j < MTOP; ++j) top[j] = 0u;
+    CUSA_TRACE_POINT(1);
+    scan([&](uint32_t key, int, bool valid) {
+        uint32_t x = valid ? key : 0u;
+#pragma unroll
+        for (int j = 0; j < MTOP; ++j) {
+            const uint32_t hi = top[j] > x ? top[j] : x;
+            x = top[j] > x ? x : top[j];
+            top[j] = hi;
+        }
+    });
+    for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
+    if (threadIdx.x == 0) {
+        st.prefix = 0;
+        st.need = k_eff;
+        st.count_eq = 0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < MTOP; ++j) atomicAdd(&hist[top[j] >> 21], 1);
+    __syncthreads();
+    pick_digit<2048>(hist, scratch, &st, 21);
+    const uint32_t d0 = st.prefix >> 21;
+    __syncthreads();
+
+    CUSA_TRACE_POINT(2);
     // 1. score key of the k_eff-th best
-    radix_select(Lc, k_eff,
-                 [&](int t, uint32_t* key) { *key = score_key(row[t]); return true; },
+    radix_select(k_eff, d0, scan, [](uint32_t skey, int, uint32_t* key) { *key = skey; return true; },
                  hist, scratch, &st);
     const uint32_t T = st.prefix;
     const int need_eq = st.need, count_eq = st.count_eq;
     __syncthreads();
 
+    CUSA_TRACE_POINT(3);
     // 2. position bound among the ties (rare: only when ties straddle the cut)
     uint32_t pos_bound = 0xffffffffu;                  // take every tie
     if (count_eq > need_eq) {
-        radix_select(Lc, need_eq,
-                     [&](int t, uint32_t* key) { *key = ~(uint32_t)t; return score_key(row[t]) == T; },
+        radix_select(need_eq, 0u, scan,
+                     [T](uint32_t skey, int t, uint32_t* key) { *key = ~(uint32_t)t; return skey == T; },
                      hist, scratch, &st);
         pos_bound = ~st.prefix;                        // need_eq-th smallest tying position
         __syncthreads();
     }
 
+    CUSA_TRACE_POINT(4);
     // 3. compact the survivors (any order), pad, sort descending
     if (threadIdx.x == 0) n_out = 0;
     __syncthreads();                                   // also: histogram no longer needed
-    for (int base = 0; base < Lc; base += SEL_THREADS) {
-        const int t = base + threadIdx.x;
-        bool sel = false;
-        uint32_t key = 0;
-        if (t < Lc) {
-            key = score_key(row[t]);
-            sel = key > T || (key == T && (uint32_t)t <= pos_bound);
-        }
+    scan([&](uint32_t key, int t, bool valid) {
+        const bool sel = valid && (key > T || (key == T && (uint32_t)t <= pos_bound));
         const uint64_t ballot = __ballot(sel);
         int wave_base = 0;
         if (lane_id() == 0 && ballot) wave_base = atomicAdd(&n_out, __popcll(ballot));
@@ -316,57 +402,76 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
             const int slot = wave_base + mbcnt(ballot);
             if (slot < nsort) sort_buf[slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
         }
-    }
+    });
     __syncthreads();
+    CUSA_TRACE_POINT(5);
     for (int i = k_eff + threadIdx.x; i < nsort; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
-    for (int size = 2; size <= nsort; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int p = threadIdx.x; p < (nsort >> 1); p += SEL_THREADS) {
-                const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
-                const int hi = lo + stride;
-                const uint64_t a = sort_buf[lo], c = sort_buf[hi];
-                const bool desc = (lo & size) == 0;
-                if ((a < c) == desc) {
-                    sort_buf[lo] = c;
-                    sort_buf[hi] = a;
+    // Bitonic network.  Wave w owns the aligned block of nsort/16 elements [w*blk, (w+1)*blk): a
+    // step whose stride is below blk pairs elements of one block only, so it needs no workgroup
+    // barrier -- a wave's LDS accesses are performed in program order -- and only the few steps
+    // with larger strides synchronise the workgroup.
+    {
+        const int blk = nsort / SEL_WAVES, w = wave_id(), lane = lane_id();
+        for (int size = 2; size <= nsort; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                const bool local = stride < blk;
+                if (!local) __syncthreads();
+                for (int p = w * (blk >> 1) + lane; p < (w + 1) * (blk >> 1); p += 64) {
+                    const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
+                    const int hi = lo + stride;
+                    const uint64_t a = sort_buf[lo], c = sort_buf[hi];
+                    const bool desc = (lo & size) == 0;
+                    if ((a < c) == desc) {
+                        sort_buf[lo] = c;
+                        sort_buf[hi] = a;
+                    }
+                }
+                if (!local) {
+                    __syncthreads();
+                } else {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
 
+    CUSA_TRACE_POINT(6);
     // 4. rank-major output
     int32_t* __restrict__ out = rho_head + (int64_t)b * k * H + h;
     for (int j = threadIdx.x; j < k_eff; j += SEL_THREADS)
         out[(int64_t)j * H] = (int32_t)~(uint32_t)sort_buf[j];
+    CUSA_TRACE_POINT(7);
 }
 
 // ---------------------------------------------------------------- union / rank / window
 //
 // One 1024-thread workgroup per sequence.  Slot s = j*H + h of the rank-major
 // array is head h's rank-j pick; a token's global rank is the smallest slot that
-// names it.  first[t] = that slot (atomicMin, order-independent); a slot is the
+// names it.  first[t] = that slot (atomic min, order-independent); a slot is the
 // "first occurrence" of its token iff first[rho[s]] == s; the cut slot s* is the
 // one at which the count of first occurrences reaches K-W; rho's historical part
 // is {t : first[t] <= s*}, emitted in ascending position order, followed by the
 // window {L-W .. L-1}.
+// The table lives in LDS when the candidate range fits (LDS_TABLE), otherwise in
+// the workspace.  Every loop issues eight independent loads before it consumes them.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// slot s is the first (lowest) slot naming its token
-__device__ __forceinline__ bool is_first(const int32_t* first, const int32_t* rho, int s, int Lc) {
-    const uint32_t tok = (uint32_t)rho[s];
-    return tok < (uint32_t)Lc && ld_relaxed(&first[tok]) == s;
-}
+constexpr int UNION_UNROLL = 8;
 
+template <bool LDS_TABLE>
 __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __restrict__ rho_head,
                                                              const int32_t* __restrict__ seq_lens,
                                                              int32_t* first_all, int64_t ld_first,
                                                              int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
                                                              int H, int k, int budget, int window) {
+    extern __shared__ int32_t lds_first[];
     __shared__ int wave_cnt[SEL_WAVES];
     __shared__ int s_star;
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -381,28 +486,61 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     const int k_eff = k < Lc ? k : Lc;
     const int S = k_eff * H;
     const int n_hist = budget - window;
-    int32_t* first = first_all + (int64_t)b * ld_first;
+    int32_t* gfirst = first_all + (int64_t)b * ld_first;
     const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
 
-    for (int t = tid; t < Lc; t += SEL_THREADS) first[t] = 0x7fffffff;
-    __threadfence();
+    auto tbl_set = [&](int t, int v) { if constexpr (LDS_TABLE) lds_first[t] = v; else gfirst[t] = v; };
+    auto tbl_min = [&](int t, int v) { if constexpr (LDS_TABLE) atomicMin(&lds_first[t], v); else atomicMin(&gfirst[t], v); };
+    auto tbl_get = [&](int t) { if constexpr (LDS_TABLE) return lds_first[t]; else return ld_relaxed(&gfirst[t]); };
+
+    for (int t = tid; t < Lc; t += SEL_THREADS) tbl_set(t, 0x7fffffff);
+    if (!LDS_TABLE) __threadfence();
     __syncthreads();
-    for (int s = tid; s < S; s += SEL_THREADS) {
-        const uint32_t tok = (uint32_t)rho[s];
-        if (tok < (uint32_t)Lc) atomicMin(&first[tok], s);     // a pick is always a candidate position
+    for (int s0 = 0; s0 < S; s0 += UNION_UNROLL * SEL_THREADS) {
+        int tok[UNION_UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNION_UNROLL; ++u) {
+            const int s = s0 + u * SEL_THREADS + tid;
+            const int v = rho[s < S ? s : S - 1];                         // clamped: loads stay unconditional
+            tok[u] = s < S ? v : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < UNION_UNROLL; ++u) {
+            const int s = s0 + u * SEL_THREADS + tid;
+            if ((uint32_t)tok[u] < (uint32_t)Lc) tbl_min(tok[u], s);   // a pick is always a candidate position
+        }
     }
-    __threadfence();
+    if (!LDS_TABLE) __threadfence();
     __syncthreads();
 
-    // cut slot: each wave owns a contiguous run of slots, walked 64 at a time
+    // cut slot: each wave owns a contiguous run of slots, walked 64 at a time; `visit`
+    // hands every 64-slot group's first-occurrence ballot to f(s0, ballot)
     const int seg = ((S + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
     const int s_lo = w * seg, s_hi = (s_lo + seg < S) ? s_lo + seg : S;
+    auto visit_slots = [&](auto f) {
+        for (int g0 = s_lo; g0 < s_hi; g0 += 64 * UNION_UNROLL) {
+            int tok[UNION_UNROLL], fs[UNION_UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNION_UNROLL; ++u) {
+                const int s = g0 + u * 64 + lane;
+                const int v = rho[s < s_hi ? s : S - 1];
+                tok[u] = s < s_hi ? v : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < UNION_UNROLL; ++u) {
+                const bool ok = (uint32_t)tok[u] < (uint32_t)Lc;
+                const int v = tbl_get(ok ? tok[u] : 0);
+                fs[u] = ok ? v : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < UNION_UNROLL; ++u) {
+                const int s = g0 + u * 64 + lane;
+                f(g0 + u * 64, __ballot(s < s_hi && fs[u] == s));
+            }
+        }
+    };
     int mine = 0;
-    for (int s0 = s_lo; s0 < s_hi; s0 += 64) {
-        const int s = s0 + lane;
-        const bool f = s < s_hi && is_first(first, rho, s, Lc);
-        mine += __popcll(__ballot(f));
-    }
+    visit_slots([&](int, uint64_t ballot) { mine += __popcll(ballot); });
     if (lane == 0) wave_cnt[w] = mine;
     if (tid == 0) s_star = -1;
     __syncthreads();
@@ -414,16 +552,13 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     const int n_take = n_hist < total ? n_hist : total;   // == n_hist whenever k >= K-W
     if (n_take > 0 && before < n_take && n_take <= before + mine) {
         int run = before;
-        for (int s0 = s_lo; s0 < s_hi; s0 += 64) {
-            const int s = s0 + lane;
-            const bool f = s < s_hi && is_first(first, rho, s, Lc);
-            const uint64_t ballot = __ballot(f);
+        visit_slots([&](int g, uint64_t ballot) {
             const int c = __popcll(ballot);
             if (run < n_take && n_take <= run + c) {
-                if (f && run + mbcnt(ballot) + 1 == n_take) s_star = s;
+                if (((ballot >> lane) & 1) && run + mbcnt(ballot) + 1 == n_take) s_star = g + lane;
             }
             run += c;
-        }
+        });
     }
     __syncthreads();
     const int cut = s_star;
@@ -431,24 +566,31 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     // ascending emission: each wave owns a contiguous run of positions
     const int pseg = ((Lc + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
     const int p_lo = w * pseg, p_hi = (p_lo + pseg < Lc) ? p_lo + pseg : Lc;
+    auto visit_pos = [&](auto f) {
+        for (int g0 = p_lo; g0 < p_hi; g0 += 64 * UNION_UNROLL) {
+            int fv[UNION_UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNION_UNROLL; ++u) {
+                const int t = g0 + u * 64 + lane;
+                const int v = tbl_get(t < p_hi ? t : Lc - 1);
+                fv[u] = t < p_hi ? v : 0x7fffffff;
+            }
+#pragma unroll
+            for (int u = 0; u < UNION_UNROLL; ++u) f(g0 + u * 64, __ballot(fv[u] <= cut));
+        }
+    };
     int sel_cnt = 0;
-    for (int t0 = p_lo; t0 < p_hi; t0 += 64) {
-        const int t = t0 + lane;
-        const bool f = t < p_hi && ld_relaxed(&first[t]) <= cut;
-        sel_cnt += __popcll(__ballot(f));
-    }
+    visit_pos([&](int, uint64_t ballot) { sel_cnt += __popcll(ballot); });
     __syncthreads();                                      // wave_cnt reuse
     if (lane == 0) wave_cnt[w] = sel_cnt;
     __syncthreads();
     int off = 0;
     for (int i = 0; i < w; ++i) off += wave_cnt[i];
-    for (int t0 = p_lo; t0 < p_hi; t0 += 64) {
-        const int t = t0 + lane;
-        const bool f = t < p_hi && ld_relaxed(&first[t]) <= cut;
-        const uint64_t ballot = __ballot(f);
-        if (f && off + mbcnt(ballot) < n_hist) out[off + mbcnt(ballot)] = t;
+    visit_pos([&](int g, uint64_t ballot) {
+        const int slot = off + mbcnt(ballot);
+        if (((ballot >> lane) & 1) && slot < n_hist) out[slot] = g + lane;
         off += __popcll(ballot);
-    }
+    });
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;
 }
@@ -484,19 +626,6 @@ __device__ __forceinline__ float row_sum16(float v) {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-#ifdef CUSA_TRACE
-__device__ unsigned long long g_trace[8192 * 8];
-#define CUSA_TRACE_POINT(slot)                                                                         \
-    do {                                                                                               \
-        if (threadIdx.x == 0) {                                                                        \
-            int wg_ = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);                  \
-            if (wg_ < 8192) g_trace[wg_ * 8 + (slot)] = wall_clock64();                                \
-        }                                                                                              \
-    } while (0)
-#else
-#define CUSA_TRACE_POINT(slot) do {} while (0)
-#endif
 
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_WAVES = 4;
