@@ -17,8 +17,8 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_QF32 = 0, KID_SCORE, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_COUNT };
-const char* const kKernelNames[KID_COUNT] = {"q_to_f32_kernel", "score_kernel", "topk_kernel", "union_kernel",
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_COUNT };
+const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel"};
 
 struct ProfRec {
@@ -131,6 +131,7 @@ KvView make_view(const cusa_params* p, const cusa_kv* kv) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+constexpr int SCORE_GRID = 512;    // persistent scoring workgroups: 2 per CU on 256 CUs
 constexpr int MAX_SPLITS = 256;
 constexpr int TARGET_WGS = 1024;
 
@@ -156,7 +157,7 @@ AttnPlan plan_attn(int n_max, int BG, int g) {
 }
 
 struct WsLayout {
-    size_t qf, scores, rho_head, first, part_acc, part_ml, total;
+    size_t scores, rho_head, first, part_acc, part_ml, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -175,7 +176,6 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     int ms2 = plan_attn(p->budget > 0 ? p->budget : 1, BG, g).n_splits;
     w.max_splits = ms > ms2 ? ms : ms2;
     size_t off = 0;
-    w.qf = off;        off += align256((size_t)(B * H * D) * 4);
     w.scores = off;    off += align256((size_t)(B * H * w.ldp) * 4);
     w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);
     w.first = off;     off += align256((size_t)(B * w.ldp) * 4);
@@ -293,12 +293,12 @@ cusa_status launch_topk(dim3 grid, size_t shmem, hipStream_t s, const float* P, 
 }
 
 template <int GQ>
-void launch_score(bool paged, dim3 grid, hipStream_t s, const KvView& view, const float* qf, float* P, int64_t ldp,
-                  int H, int budget, int window) {
+void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
+                  int H, int budget, int window, int tiles_per_seq, int n_tiles) {
     if (paged)
-        score_kernel<GQ, true><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window);
+        score_kernel<GQ, true><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
     else
-        score_kernel<GQ, false><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window);
+        score_kernel<GQ, false><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
 }
 
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
@@ -306,27 +306,25 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
     const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
     const KvView view = make_view(p, kv);
     const bool paged = kv->layout == CUSA_KV_PAGED;
-    float* qf = ws_ptr<float>(ws, w.qf);
+    const uint16_t* qf = static_cast<const uint16_t*>(q);
     float* P = ws_ptr<float>(ws, w.scores);
     int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
     int32_t* first = ws_ptr<int32_t>(ws, w.first);
 
     if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
-        const int nq = B * H * D;
-        {
-            ProfScope ps(KID_QF32, s);
-            q_to_f32_kernel<<<(nq + 255) / 256, 256, 0, s>>>(static_cast<const uint16_t*>(q), qf, nq);
-        }
-        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         const int lc_max = kv->max_seq_len - p->window;
-        dim3 grid((lc_max + SCORE_ROWS - 1) / SCORE_ROWS, p->n_kv_heads, B);
+        const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
+        const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
+        if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
+        const int n_tiles = (int)n_tiles64;
+        const int grid = n_tiles < SCORE_GRID ? n_tiles : SCORE_GRID;   // two 64 KB tiles fit a CU's LDS
         {
             ProfScope ps(KID_SCORE, s);
             switch (g) {
-                case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
-                case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
-                case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
-                default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window); break;
+                case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
             }
         }
         if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;

@@ -1,9 +1,8 @@
 // Device code of libcusa: gfx950 kernels for the CUSA decode hot path.
 //
-//   q_to_f32_kernel     widen q to binary32 so the scoring kernel can read it
-//                       through the scalar cache
 //   score_kernel        P = q.K^T over the candidate range (Alg. 1, selection
-//                       layer), one lane per key row, K staged through LDS
+//                       layer), one lane per key row, K staged through LDS,
+//                       products accumulated by k = 1 MFMA in column order
 //   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on
 //                       order-preserving keys, then a bitonic sort in LDS
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
@@ -54,6 +53,10 @@ __device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int kvh, 
     return (int64_t)b * kv.sb + (int64_t)kvh * kv.sh + (int64_t)pos * kv.st;
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -71,77 +74,126 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// ---------------------------------------------------------------- q -> binary32
-
-__global__ void q_to_f32_kernel(const uint16_t* __restrict__ q, float* __restrict__ qf, int n) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) qf[i] = __uint_as_float((uint32_t)q[i] << 16);
-}
-
 // ---------------------------------------------------------------- scoring pass
 //
-// One workgroup scores 256 consecutive candidate keys of one KV head against the
-// GQ query heads of its group.  The 64 KB tile is fetched with coalesced 16-byte
-// loads (16 lanes per 256-byte row) and parked in LDS; then every lane owns one
-// row and runs the left-to-right binary32 FMA chain over the 128 elements, the
-// summation order the selection's bit-exactness rests on (a bf16*bf16 product is
-// exact in binary32, so fma(q,k,acc) rounds once, like acc + q*k).  q comes from
-// the scalar cache (wave-uniform addresses), so the inner loop is pure FMA.
-// LDS chunk c of row r sits at slot c ^ (r & 7): row reads by consecutive lanes
-// then fall into distinct 16-byte bank groups.
+// A tile is 256 consecutive candidate keys of one KV head (64 KB), scored against the GQ
+// query heads of its group.  The tile is fetched with coalesced 16-byte loads (16 lanes per
+// 256-byte row) and parked in LDS, chunk c of row r at slot c ^ (r & 7) so that row reads by
+// consecutive lanes fall into distinct 16-byte bank groups.  Then every lane owns one row.
+//
+// The dot products run on the matrix cores with V_MFMA_F32_4X4X1_16B_F32: one instruction
+// takes, per lane, one binary32 element of q (head = lane % 4) and one of K (the lane's row)
+// and adds the 4 heads x 64 rows of single products to the accumulators.  With k = 1 there
+// is exactly one product (exact: bf16 x bf16 has a 16-bit significand) and one rounded
+// addition per instruction, so walking the 128 columns in order is the left-to-right
+// binary32 sum the selection's bit-exactness rests on -- no reordering inside the
+// instruction can occur.  (Checked bit for bit against a scalar fmaf chain on the device.)
+// q sits in LDS as binary32, head stride padded to 132 floats (distinct banks per head).
+//
+// A workgroup walks tiles id = blockIdx.x, +gridDim.x, ... (id = (sequence, KV head, tile)
+// in that order) and issues the loads of its next tile before it scores the current one,
+// so a CU always has loads in flight.  Rows past the candidate range are clamped to the
+// last candidate (loads stay unconditional and batched); their scores are not stored.
 
 constexpr int SCORE_ROWS = 256;
 
 template <int GQ, bool PAGED>
-__global__ __launch_bounds__(256) void score_kernel(KvView kv, const float* __restrict__ qf,
+__global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint16_t* __restrict__ q,
                                                      float* __restrict__ P, int64_t ldp, int H,
-                                                     int budget, int window) {
-    __shared__ uint4 tile[SCORE_ROWS * 16];
-    const int b = blockIdx.z, kvh = blockIdx.y, tid = threadIdx.x;
-    const int L = kv.seq_lens[b];
-    if (L <= budget) return;                      // rho = everything, nothing to score
-    const int Lc = L - window;
-    const int t0 = blockIdx.x * SCORE_ROWS;
-    if (t0 >= Lc) return;
+                                                     int budget, int window, int tiles_per_seq, int n_tiles) {
+    constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
+    constexpr int QS = 132;                           // padded head stride of q in LDS
+    constexpr int QN = (GQ * D + 255) / 256;          // q elements staged per thread
+    __shared__ u32x4 tile[SCORE_ROWS * 16];
+    __shared__ float qs[SETS * 4 * QS];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int G = kv.G;
+    for (int i = tid; i < SETS * 4 * QS; i += 256) qs[i] = 0.0f;   // heads beyond GQ contribute zeros
 
-    uint4 stage[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int chunk = i * 256 + tid;
-        const int row = chunk >> 4, c = chunk & 15;
-        const int t = t0 + row;
-        stage[i] = make_uint4(0, 0, 0, 0);
-        if (t < Lc) {
-            const uint16_t* p = kv.k + row_offset<PAGED>(kv, b, kvh, t) + c * 8;
-            stage[i] = *reinterpret_cast<const uint4*>(p);
+    // next tile at or after `id` (stride gridDim.x) that has candidates; n_tiles if none
+    auto next_valid = [&](int id, int& b, int& kvh, int& t0, int& Lc) __attribute__((always_inline)) {
+        for (; id < n_tiles; id += gridDim.x) {
+            const int seq_head = id / tiles_per_seq;
+            b = seq_head / G;
+            kvh = seq_head - b * G;
+            t0 = (id - seq_head * tiles_per_seq) * SCORE_ROWS;
+            const int L = kv.seq_lens[b];
+            Lc = L - window;
+            if (L > budget && t0 < Lc) return id;     // L <= budget: rho = everything, nothing to score
         }
-    }
+        return n_tiles;
+    };
+    int b = 0, kvh = 0, t0 = 0, Lc = 0;               // tile being scored (none yet)
+    bool have_cur = false;
+    int nb, nkvh, nt0, nLc;
+    int nid = next_valid(blockIdx.x, nb, nkvh, nt0, nLc);
+    while (true) {
+        const bool have_next = nid < n_tiles;
+        u32x4 stage[16];
+        uint16_t qstage[QN];
+        if (have_next) {                              // loads of the next tile, in flight during the scoring below
+            int64_t off[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int chunk = i * 256 + tid;
-        const int row = chunk >> 4, c = chunk & 15;
-        tile[row * 16 + (c ^ (row & 7))] = stage[i];
-    }
-    __syncthreads();
-
-    const float* __restrict__ qg = qf + ((int64_t)b * H + (int64_t)kvh * GQ) * D;
-    float acc[GQ];
+            for (int i = 0; i < 16; ++i) {
+                const int chunk = i * 256 + tid;
+                const int t = min(nt0 + (chunk >> 4), nLc - 1);
+                off[i] = row_offset<PAGED>(kv, nb, nkvh, t) + (chunk & 15) * 8;
+            }
 #pragma unroll
-    for (int h = 0; h < GQ; ++h) acc[h] = 0.0f;
+            for (int i = 0; i < 16; ++i) stage[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
+            const uint16_t* __restrict__ qg = q + ((int64_t)nb * H + (int64_t)nkvh * GQ) * D;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const uint4 w = tile[tid * 16 + (c ^ (tid & 7))];
-        float kf[8];
-        unpack8(w, kf);
+            for (int j = 0; j < QN; ++j) qstage[j] = qg[min(j * 256 + tid, GQ * D - 1)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (have_cur) {
+            f32x4 acc[SETS];
 #pragma unroll
-        for (int h = 0; h < GQ; ++h)
+            for (int s = 0; s < SETS; ++s) acc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h] = __builtin_fmaf(qg[h * D + c * 8 + e], kf[e], acc[h]);
-    }
-    const int t = t0 + tid;
-    if (t < Lc) {
+            for (int c = 0; c < 16; ++c) {
+                const u32x4 w = tile[tid * 16 + (c ^ (tid & 7))];
+                float kf[8];
+                unpack8(make_uint4(w.x, w.y, w.z, w.w), kf);
 #pragma unroll
-        for (int h = 0; h < GQ; ++h) P[((int64_t)b * H + kvh * GQ + h) * ldp + t] = acc[h];
+                for (int half = 0; half < 2; ++half) {
+                    f32x4 qa[SETS];
+#pragma unroll
+                    for (int s = 0; s < SETS; ++s)
+                        qa[s] = *reinterpret_cast<const f32x4*>(&qs[(s * 4 + (lane & 3)) * QS + c * 8 + half * 4]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int s = 0; s < SETS; ++s)
+                            acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qa[s][e], kf[half * 4 + e], acc[s], 0, 0, 0);
+                }
+            }
+            const int t = t0 + tid;
+            if (t < Lc) {
+#pragma unroll
+                for (int s = 0; s < SETS; ++s)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (s * 4 + r < GQ) P[((int64_t)b * H + kvh * GQ + s * 4 + r) * ldp + t] = acc[s][r];
+            }
+        }
+        if (!have_next) break;
+        __syncthreads();                              // everyone is done reading the tile in LDS
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int chunk = i * 256 + tid;
+            const int row = chunk >> 4, c = chunk & 15;
+            tile[row * 16 + (c ^ (row & 7))] = stage[i];
+        }
+#pragma unroll
+        for (int j = 0; j < QN; ++j) {
+            const int i = j * 256 + tid;
+            if (i < GQ * D) qs[(i >> 7) * QS + (i & (D - 1))] = __uint_as_float((uint32_t)qstage[j] << 16);
+        }
+        __syncthreads();
+        b = nb; kvh = nkvh; t0 = nt0; Lc = nLc;
+        have_cur = true;
+        nid = next_valid(nid + gridDim.x, nb, nkvh, nt0, nLc);
     }
 }
 
@@ -623,9 +675,6 @@ __device__ __forceinline__ float row_sum16(float v) {
     v += dpp_move<0x140>(v);   // row_mirror
     return v;
 }
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_WAVES = 4;
