@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -144,10 +145,13 @@ struct AttnPlan {
 AttnPlan plan_attn(int n_max, int BG, int g) {
     AttnPlan pl;
     const int64_t tiles128 = ((int64_t)n_max + 127) / 128 * BG;
-    pl.ti = (g <= 4 && tiles128 >= 512) ? 8 : 4;
+    pl.ti = tiles128 >= 512 ? 8 : 4;
+    (void)g;
     const int wg_tile = pl.ti * 4 * ATTN_WAVES;
     int by_work = (n_max + wg_tile - 1) / wg_tile;
-    int target = TARGET_WGS / BG;
+    int target_wgs = TARGET_WGS;
+    if (const char* e = getenv("CUSA_TARGET_WGS")) target_wgs = atoi(e);   // TEMP tuning hook
+    int target = target_wgs / BG;
     if (target < 1) target = 1;
     int s = by_work < target ? by_work : target;
     if (s < 1) s = 1;
@@ -214,11 +218,9 @@ template <int GQ, bool SPARSE>
 void launch_attn_ti(int ti, bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                     const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
                     uint16_t* out, int n_splits, int H) {
-    if constexpr (GQ <= 4) {
-        if (ti == 8) {
-            launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
-            return;
-        }
+    if (ti == 8) {
+        launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
+        return;
     }
     launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
 }

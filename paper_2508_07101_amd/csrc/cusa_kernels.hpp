@@ -650,12 +650,14 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 // ---------------------------------------------------------------- attention (split-K flash-decode)
 //
 // grid (n_splits, G, B), 256 threads.  A workgroup owns a contiguous run of the
-// sequence's token list (all tokens, or rho) for one KV head and keeps the GQ
-// query heads of that group in registers (pre-multiplied by sm_scale*log2 e).
-// A 256-byte K or V row is read by 16 lanes with one 16-byte load each; a wave
-// therefore covers 4 rows per load instruction and TI*4 rows per iteration.
-// q.k is finished with a 16-lane DPP butterfly, softmax is the usual running
-// (max, sum) rescale per iteration, and P.V accumulates 8 columns per lane.
+// sequence's token list (all tokens, or rho) for one KV head; the GQ query heads of
+// that group sit in LDS as bf16.  A 256-byte K or V row is read by 16 lanes with one
+// 16-byte load each; a wave therefore covers 4 rows per load instruction and TI*4
+// rows per iteration.  The wave parks its K rows in LDS and re-reads them one row per
+// lane, which is the operand layout of the 4x4x4 bf16 MFMA: 32 instructions give every
+// lane the scores of its token for four heads.  Softmax is the usual running (max, sum)
+// rescale per iteration with one exp per (token, head); the numerators go back through
+// LDS to the lanes that hold that token's V row, and P.V accumulates 8 columns per lane.
 // The four waves are merged through LDS into one partial (m, l, acc[128]) per
 // head.  With one split that is the result and is written as bf16; otherwise the
 // partial goes to the workspace and attn_reduce_kernel merges the splits.  (A merge
@@ -665,6 +667,15 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// max over the 16 lanes of a DPP row; every lane of the row gets the result
+__device__ __forceinline__ float row_max16(float v) {
+    v = fmaxf(v, dpp_move<0xB1>(v));
+    v = fmaxf(v, dpp_move<0x4E>(v));
+    v = fmaxf(v, dpp_move<0x141>(v));
+    v = fmaxf(v, dpp_move<0x140>(v));
+    return v;
 }
 
 // sum over the 16 lanes of a DPP row; every lane of the row gets the result
@@ -684,16 +695,32 @@ __host__ __device__ inline int attn_chunk(int n, int n_splits, int wg_tile) {
     return (c + wg_tile - 1) / wg_tile * wg_tile;
 }
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// LDS written by some lanes of a wave and read by others of the same wave: a wave's LDS
+// accesses are performed in program order, so only the compiler has to be kept from
+// reordering them.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int GQ, int TI, bool SPARSE, bool PAGED>
 __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
     float* __restrict__ part_ml, uint16_t* __restrict__ out, int n_splits, int H) {
-    constexpr int TILE = TI * 4;
+    constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
+    constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
+    constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
     __shared__ float sm_acc[ATTN_WAVES][GQ][D];
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
+    __shared__ u32x4 ktile[ATTN_WAVES][TILE * 16];    // a wave's K rows, chunk c of row r at slot c ^ (r & 7)
+    __shared__ f32x4 pbuf[ATTN_WAVES][TILE][SETS];    // a wave's softmax numerators, by token
+    __shared__ __attribute__((aligned(16))) uint16_t qlds[SETS * 4 * QSB];
 
     CUSA_TRACE_POINT(0);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -704,15 +731,19 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     const int begin = split * chunk;
     const int end = (begin + chunk < n) ? begin + chunk : n;
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
+    const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
 
-    float qr[GQ][8];
-#pragma unroll
-    for (int h = 0; h < GQ; ++h) {
-        const uint4 w = *reinterpret_cast<const uint4*>(q + ((int64_t)b * H + kvh * GQ + h) * D + c * 8);
-        unpack8(w, qr[h]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qr[h][e] *= scale_log2e;
+    for (int i = tid; i < SETS * 4 * D; i += ATTN_THREADS) {
+        const int h = i >> 7, col = i & (D - 1);
+        qlds[h * QSB + col] = h < GQ ? q[(head0 + h) * D + col] : (uint16_t)0;   // heads beyond GQ score zero
     }
+    __syncthreads();
+
+    // Scores come from V_MFMA_F32_4X4X4_16B_BF16: per lane four bf16 of q (head = lane % 4)
+    // and four of K (the lane's token); after 32 instructions lane t holds q_h . k_t for the
+    // heads of each set.  Lane t scores token t % TILE of the tile.
+    const int tl = lane % TILE;
+    const bool owner = lane < TILE;                   // lanes beyond TILE repeat a token; they add nothing to l
     float m[GQ], l[GQ], acc[GQ][8];
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
@@ -725,7 +756,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
         // Rows past the end of the run are clamped to its last token (a valid row) so that all
         // loads are unconditional and issue back to back; their scores are masked below.
-        uint4 kreg[TI], vreg[TI];
+        u32x4 kreg[TI], vreg[TI];
         int pos[TI];
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
@@ -741,60 +772,76 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         }
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
-            kreg[i] = *reinterpret_cast<const uint4*>(kv.k + off[i]);
-            vreg[i] = *reinterpret_cast<const uint4*>(kv.v + off[i]);
+            kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
+            vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
         }
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
-        float s[TI][GQ];
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
-            float kf[8];
-            unpack8(kreg[i], kf);
-            const bool valid = t0 + i * 4 + r < end;
+            const int row = i * 4 + r;
+            ktile[wave][row * 16 + (c ^ (row & 7))] = kreg[i];
+        }
+        wave_lds_sync();
+
+        f32x4 sc[SETS];
 #pragma unroll
-            for (int h = 0; h < GQ; ++h) {
-                float p = 0.0f;
+        for (int s = 0; s < SETS; ++s) sc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) p = __builtin_fmaf(qr[h][e], kf[e], p);
-                p = row_sum16(p);
-                s[i][h] = valid ? p : -INFINITY;
+        for (int cc = 0; cc < 16; ++cc) {
+            const u32x4 kw = ktile[wave][tl * 16 + (cc ^ (tl & 7))];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const uint2 kb = half == 0 ? make_uint2(kw.x, kw.y) : make_uint2(kw.z, kw.w);
+                const s16x4 bq = __builtin_bit_cast(s16x4, kb);
+#pragma unroll
+                for (int s = 0; s < SETS; ++s) {
+                    const s16x4 aq = *reinterpret_cast<const s16x4*>(&qlds[(s * 4 + (lane & 3)) * QSB + cc * 8 + half * 4]);
+                    sc[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aq, bq, sc[s], 0, 0, 0);
+                }
             }
         }
+        const bool valid = t0 + tl < end;
+        float corr[GQ];
 #pragma unroll
         for (int h = 0; h < GQ; ++h) {
-            float mt = s[0][h];
-#pragma unroll
-            for (int i = 1; i < TI; ++i) mt = fmaxf(mt, s[i][h]);
+            const float z = valid ? sc[h >> 2][h & 3] * scale_log2e : -INFINITY;
+            float mt = row_max16(z);
             mt = fmaxf(mt, __shfl_xor(mt, 16));
             mt = fmaxf(mt, __shfl_xor(mt, 32));
             const float m_new = fmaxf(m[h], mt);      // finite: token t0 of this tile is valid
-            const float corr = exp2f(m[h] - m_new);
-            l[h] *= corr;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+            corr[h] = exp2f(m[h] - m_new);
             m[h] = m_new;
-#pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                const float p = exp2f(s[i][h] - m_new);
-                l[h] += p;
-                s[i][h] = p;
-            }
+            const float pz = exp2f(z - m_new);
+            l[h] = l[h] * corr[h] + (owner ? pz : 0.0f);
+            sc[h >> 2][h & 3] = pz;
         }
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) pbuf[wave][tl][s] = sc[s];
+#pragma unroll
+        for (int h = 0; h < GQ; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= corr[h];
+        wave_lds_sync();
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
             float vf[8];
-            unpack8(vreg[i], vf);
+            unpack8(make_uint4(vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w), vf);
+            f32x4 pv[SETS];
+#pragma unroll
+            for (int s = 0; s < SETS; ++s) pv[s] = pbuf[wave][i * 4 + r][s];
 #pragma unroll
             for (int h = 0; h < GQ; ++h)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(s[i][h], vf[e], acc[h][e]);
+                for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pv[h >> 2][h & 3], vf[e], acc[h][e]);
         }
+        wave_lds_sync();                              // the tile buffers are rewritten next iteration
     }
 
     CUSA_TRACE_POINT(1);
     // merge the wave's four row groups, then the four waves
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
+        l[h] = row_sum16(l[h]);
         l[h] += __shfl_xor(l[h], 16);
         l[h] += __shfl_xor(l[h], 32);
 #pragma unroll
@@ -812,7 +859,6 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         }
     }
     __syncthreads();
-    const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
     for (int o = tid; o < GQ * D; o += ATTN_THREADS) {
         const int h = o / D, col = o % D;
         float M = sm_m[0][h];
