@@ -5,7 +5,6 @@
 
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -134,29 +133,35 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 constexpr int SCORE_GRID = 512;    // persistent scoring workgroups: 2 per CU on 256 CUs
 constexpr int MAX_SPLITS = 256;
-constexpr int TARGET_WGS = 1024;
+constexpr int TARGET_WGS = 512;     // two resident workgroups per CU
+constexpr int CHUNK_CAP = 4096;
 
 struct AttnPlan {
     int ti;        // row-load instructions per wave iteration (4 or 8)
-    int n_splits;
+    int chunk;     // tokens per workgroup, a multiple of the workgroup tile
+    int n_splits;  // grid.x = ceil(n_max / chunk)
 };
 
-// Split count and tile depth for n_max tokens per (sequence, KV head).
+// Workgroup granularity for n_max tokens per (sequence, KV head): about TARGET_WGS workgroups
+// when every sequence has n_max tokens, but never more than CHUNK_CAP tokens per workgroup, so
+// that a large ragged batch is cut into equal pieces instead of one piece per sequence.
 AttnPlan plan_attn(int n_max, int BG, int g) {
+    (void)g;
     AttnPlan pl;
     const int64_t tiles128 = ((int64_t)n_max + 127) / 128 * BG;
     pl.ti = tiles128 >= 512 ? 8 : 4;
-    (void)g;
     const int wg_tile = pl.ti * 4 * ATTN_WAVES;
-    int by_work = (n_max + wg_tile - 1) / wg_tile;
-    int target_wgs = TARGET_WGS;
-    if (const char* e = getenv("CUSA_TARGET_WGS")) target_wgs = atoi(e);   // TEMP tuning hook
-    int target = target_wgs / BG;
-    if (target < 1) target = 1;
-    int s = by_work < target ? by_work : target;
-    if (s < 1) s = 1;
-    if (s > MAX_SPLITS) s = MAX_SPLITS;
-    pl.n_splits = s;
+    const int target_wgs = TARGET_WGS;
+    int64_t chunk = ((int64_t)n_max * BG + target_wgs - 1) / target_wgs;
+    if (chunk > CHUNK_CAP) chunk = CHUNK_CAP;
+    chunk = (chunk + wg_tile - 1) / wg_tile * wg_tile;
+    if ((n_max + chunk - 1) / chunk > MAX_SPLITS) {
+        chunk = ((int64_t)n_max + MAX_SPLITS - 1) / MAX_SPLITS;
+        chunk = (chunk + wg_tile - 1) / wg_tile * wg_tile;
+    }
+    pl.chunk = (int)chunk;
+    pl.n_splits = (int)((n_max + chunk - 1) / chunk);
+    if (pl.n_splits < 1) pl.n_splits = 1;
     return pl;
 }
 
@@ -207,22 +212,22 @@ cusa_status launch_status() { return hipGetLastError() == hipSuccess ? CUSA_OK :
 template <int GQ, int TI, bool SPARSE>
 void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                          const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                         uint16_t* out, int n_splits, int H) {
+                         uint16_t* out, int n_splits, int chunk, int H) {
     if (paged)
-        attn_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
+        attn_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
     else
-        attn_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
+        attn_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
 }
 
 template <int GQ, bool SPARSE>
 void launch_attn_ti(int ti, bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                     const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                    uint16_t* out, int n_splits, int H) {
+                    uint16_t* out, int n_splits, int chunk, int H) {
     if (ti == 8) {
-        launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
+        launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
         return;
     }
-    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, H);
+    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
 }
 
 // Attention over all tokens (idx == nullptr) or over idx/cnt; n_max bounds the token count.
@@ -243,16 +248,17 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     {
         ProfScope ps(SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL, s);
         switch (g) {
-            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
-            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
-            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
-            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, H); break;
+            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
+            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
+            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
+            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
         }
     }
     if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
     if (pl.n_splits > 1) {
         ProfScope ps(KID_REDUCE, s);
-        attn_reduce_kernel<<<dim3(H, p->batch), 256, 0, s>>>(pa, pm, oo, pl.n_splits, H);
+        attn_reduce_kernel<<<dim3(H, p->batch), 256, 0, s>>>(pa, pm, oo, SPARSE ? cnt : kv->seq_lens,
+                                                             SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H);
     }
     return launch_status();
 }

@@ -690,9 +690,12 @@ __device__ __forceinline__ float row_sum16(float v) {
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_WAVES = 4;
 
-__host__ __device__ inline int attn_chunk(int n, int n_splits, int wg_tile) {
-    int c = (n + n_splits - 1) / n_splits;
-    return (c + wg_tile - 1) / wg_tile * wg_tile;
+// Workgroup `split` of a (sequence, KV head) owns tokens [split*chunk, split*chunk + chunk) of
+// the token list; a list of n tokens keeps ceil(n / chunk) workgroups busy (at least one) and
+// the others leave at once, so short sequences of a ragged batch cost nothing.
+__host__ __device__ inline int attn_active_splits(int n, int chunk) {
+    const int a = (n + chunk - 1) / chunk;
+    return a < 1 ? 1 : a;
 }
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -710,7 +713,7 @@ template <int GQ, int TI, bool SPARSE, bool PAGED>
 __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
-    float* __restrict__ part_ml, uint16_t* __restrict__ out, int n_splits, int H) {
+    float* __restrict__ part_ml, uint16_t* __restrict__ out, int n_splits, int chunk, int H) {
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
@@ -727,7 +730,8 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
     const int L = kv.seq_lens[b];
     const int n = SPARSE ? min(cnt[b], budget) : L;
-    const int chunk = attn_chunk(n, n_splits, WG_TILE);
+    const int n_active = attn_active_splits(n, chunk);   // chunk is a multiple of WG_TILE
+    if (split >= n_active) return;
     const int begin = split * chunk;
     const int end = (begin + chunk < n) ? begin + chunk : n;
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
@@ -872,7 +876,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             A = __builtin_fmaf(sm_acc[wv][h][col], f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
-        if (n_splits == 1) {                             // this workgroup saw the whole token list
+        if (n_active == 1) {                             // this workgroup saw the whole token list
             out[(head0 + h) * D + col] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
         } else {
             const int64_t p = (head0 + h) * n_splits + split;
@@ -885,16 +889,22 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     }
 }
 
-// Merge of the split-K partials.  grid (H, B), 256 threads: thread (c4, sr) owns output
+// Merge of the split-K partials of sequences that kept more than one workgroup busy.
+// grid (H, B), 256 threads: thread (c4, sr) owns output
 // columns 4*c4 .. 4*c4+3 and folds the splits sr, sr+8, ... into a running (m, l, a[4])
 // with 16-byte loads; the eight split-rows then meet in LDS and the result is written as bf16.
+// n_tok[b] is the sequence's token count (seq_lens, or cnt clipped to the budget when sparse).
 __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restrict__ part_acc,
                                                            const float* __restrict__ part_ml,
-                                                           uint16_t* __restrict__ out, int n_splits, int H) {
+                                                           uint16_t* __restrict__ out,
+                                                           const int32_t* __restrict__ n_tok, int n_clip,
+                                                           int stride_splits, int chunk, int H) {
     __shared__ float red_a[8][D];
     __shared__ float red_m[8], red_l[8];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, c4 = tid & 31, sr = tid >> 5;
-    const int64_t base = ((int64_t)b * H + h) * n_splits;
+    const int n_splits = attn_active_splits(min(n_tok[b], n_clip), chunk);
+    if (n_splits <= 1) return;                           // the attention kernel wrote the result itself
+    const int64_t base = ((int64_t)b * H + h) * stride_splits;
     constexpr int U = 4;
     float mo = -INFINITY, lo = 0.0f;
     f32x4 ao = {0.0f, 0.0f, 0.0f, 0.0f};
