@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
@@ -122,6 +124,14 @@ def main():
             r.run()
         run_step = graph.replay
     step_s = time_steps(run_step, args.steps, args.warmup, torch)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     full_s = None
     if not args.no_full_baseline:

@@ -21,15 +21,23 @@ enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPAR
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel"};
 
+// One HIP event is recorded after every kernel; a kernel's duration is the time from the
+// event that follows the previous kernel on the same stream to the event that follows it (a
+// separate start event is recorded only for the first kernel after a reset or a stream
+// change).  Sharing events keeps the measurement's own cost per launch low, so the figures
+// stay close to a kernel trace's.
 struct ProfRec {
     int id;
     hipEvent_t start, stop;
+    bool owns_start;
 };
 struct Profiler {
     std::mutex mu;
     bool on = false;
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> pool;
+    hipEvent_t last_stop = nullptr;
+    hipStream_t last_stream = nullptr;
     int64_t calls[KID_COUNT] = {0};
     double ms[KID_COUNT] = {0};
 } g_prof;
@@ -53,15 +61,23 @@ struct ProfScope {
         if (!active) return;
         std::lock_guard<std::mutex> lk(g_prof.mu);
         rec.id = id;
-        rec.start = prof_event();
+        if (g_prof.last_stop && g_prof.last_stream == stream) {
+            rec.start = g_prof.last_stop;
+            rec.owns_start = false;
+        } else {
+            rec.start = prof_event();
+            rec.owns_start = true;
+            (void)hipEventRecord(rec.start, stream);
+        }
         rec.stop = prof_event();
-        (void)hipEventRecord(rec.start, stream);
     }
     ~ProfScope() {
         if (!active) return;
         (void)hipEventRecord(rec.stop, stream);
         std::lock_guard<std::mutex> lk(g_prof.mu);
         g_prof.recs.push_back(rec);
+        g_prof.last_stop = rec.stop;
+        g_prof.last_stream = stream;
     }
 };
 
@@ -496,6 +512,7 @@ const char* cusa_profile_kernel_name(int32_t id) { return (id >= 0 && id < KID_C
 void cusa_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
     g_prof.on = on != 0;
+    g_prof.last_stop = nullptr;
 }
 
 static void prof_drain_locked() {
@@ -505,10 +522,11 @@ static void prof_drain_locked() {
             g_prof.calls[r.id] += 1;
             g_prof.ms[r.id] += ms;
         }
-        g_prof.pool.push_back(r.start);
+        if (r.owns_start) g_prof.pool.push_back(r.start);
         g_prof.pool.push_back(r.stop);
     }
     g_prof.recs.clear();
+    g_prof.last_stop = nullptr;
 }
 
 void cusa_profile_reset(void) {
