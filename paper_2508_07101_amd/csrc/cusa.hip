@@ -298,22 +298,23 @@ bool allow_dynamic_lds(const void* fn, size_t bytes) {
 }
 
 template <int ITEMS, int MTOP>
-cusa_status launch_topk_m(dim3 grid, size_t shmem, hipStream_t s, const float* P, int64_t ldp,
-                          const int32_t* seq_lens, int32_t* rho_head, int H, int k, int budget, int window,
-                          int nsort) {
+cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
+                          int32_t* rho_head, int H, int k, int budget, int window) {
+    const size_t shmem = (size_t)MTOP * SEL_THREADS * sizeof(uint64_t);
     if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
         return CUSA_ERR_LAUNCH;
-    topk_kernel<ITEMS, MTOP><<<grid, SEL_THREADS, shmem, s>>>(P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+    topk_kernel<ITEMS, MTOP><<<grid, SEL_THREADS, shmem, s>>>(P, ldp, seq_lens, rho_head, H, k, budget, window);
     return launch_status();
 }
 
-// MTOP: per-thread candidates kept for the lower bound, MTOP * 1024 >= k.
+// MTOP: composites sorted per thread (MTOP * 1024 >= k), also the number of per-thread
+// candidates kept for the lower bound.
 template <int ITEMS>
-cusa_status launch_topk(dim3 grid, size_t shmem, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                        int32_t* rho_head, int H, int k, int budget, int window, int nsort) {
-    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
-    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
-    return launch_topk_m<ITEMS, 8>(grid, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, nsort);
+cusa_status launch_topk(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
+                        int32_t* rho_head, int H, int k, int budget, int window) {
+    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
+    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
+    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
 }
 
 template <int GQ>
@@ -352,19 +353,16 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
             }
         }
         if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
-        int nsort = 1024;
-        while (nsort < w.k) nsort <<= 1;
-        const size_t shmem = (size_t)nsort * sizeof(uint64_t);
         const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
         cusa_status st;
         {
             ProfScope ps(KID_TOPK, s);
             const dim3 tg(H, B);
-            if (items <= 4) st = launch_topk<4>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
-            else if (items <= 8) st = launch_topk<8>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
-            else if (items <= 16) st = launch_topk<16>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
-            else if (items <= 32) st = launch_topk<32>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
-            else st = launch_topk<0>(tg, shmem, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window, nsort);
+            if (items <= 4) st = launch_topk<4>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
+            else if (items <= 8) st = launch_topk<8>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
+            else if (items <= 16) st = launch_topk<16>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
+            else if (items <= 32) st = launch_topk<32>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
+            else st = launch_topk<0>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
         }
         if (st != CUSA_OK) return st;
     }

@@ -302,8 +302,10 @@ __device__ __forceinline__ void pick_digit(int* hist, int* scratch, SelectState*
 }
 
 // Radix select of the `need`-th largest 32-bit key among this workgroup's candidates.
-// scan(f) must call f(key, t, valid) for every candidate slot of the calling thread, the
-// same number of times in every lane of a wave.  accept(key, t) narrows the candidates.
+// scan(f) must call f(key, t) for every candidate slot of the calling thread, the same
+// number of times in every lane of a wave; slots past the candidate range carry key 0, which
+// no real score maps to and which therefore never reaches the top k.  key_map(key, t, &out)
+// narrows the candidates and chooses the key that is selected on.
 // Leaves the key in st->prefix, the number still wanted among equal keys in st->need and
 // their count in st->count_eq.
 // Keys whose top digit is below min_digit0 are known not to matter and are not counted.
@@ -325,9 +327,9 @@ __device__ __forceinline__ void radix_select(int need, uint32_t min_digit0, Scan
         const int shift = shifts[pass];
         const uint32_t dmask = (1u << bits[pass]) - 1u;
         const uint32_t floor_d = pass == 0 ? min_digit0 : 0u;
-        scan([&](uint32_t skey, int t, bool valid) {
+        scan([&](uint32_t skey, int t) {
             uint32_t key;
-            if (valid && key_map(skey, t, &key) && (key & mask) == prefix && ((key >> shift) & dmask) >= floor_d)
+            if (key_map(skey, t, &key) && (key & mask) == prefix && ((key >> shift) & dmask) >= floor_d)
                 atomicAdd(&hist[(key >> shift) & dmask], 1);
         });
         __syncthreads();
@@ -341,12 +343,13 @@ template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
-                                                            int budget, int window, int nsort) {
-    extern __shared__ uint64_t sort_buf[];            // nsort composites; aliases the histogram
+                                                            int budget, int window) {
+    constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
+    extern __shared__ uint64_t sort_buf[];            // NSORT composites; aliases the histogram
     __shared__ int scratch[SEL_WAVES + 1];
     __shared__ SelectState st;
     __shared__ int n_out;
-    int* hist = reinterpret_cast<int*>(sort_buf);     // 2048 ints = 8 KB <= nsort * 8 (nsort >= 1024)
+    int* hist = reinterpret_cast<int*>(sort_buf);     // 2048 ints = 8 KB <= NSORT * 8
 
     const int h = blockIdx.x, b = blockIdx.y;
     const int L = seq_lens[b];
@@ -369,8 +372,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         if constexpr (ITEMS > 0) {
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i) {
-                const int t = i * SEL_THREADS + threadIdx.x;
-                f(keys[i], t, t < Lc);
+                f(keys[i], i * SEL_THREADS + (int)threadIdx.x);
             }
         } else {
             for (int t0 = 0; t0 < Lc; t0 += 8 * SEL_THREADS) {
@@ -378,12 +380,12 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int t = t0 + u * SEL_THREADS + threadIdx.x;
-                    kk[u] = score_key(row[t < Lc ? t : Lc - 1]);          // clamped: loads stay unconditional
+                    const uint32_t kv_ = score_key(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
+                    kk[u] = t < Lc ? kv_ : 0u;
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int t = t0 + u * SEL_THREADS + threadIdx.x;
-                    f(kk[u], t, t < Lc);
+                    f(kk[u], t0 + u * SEL_THREADS + (int)threadIdx.x);
                 }
             }
         }
@@ -398,8 +400,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 #pragma unroll
     for (int j = 0; j < MTOP; ++j) top[j] = 0u;
     CUSA_TRACE_POINT(1);
-    scan([&](uint32_t key, int, bool valid) {
-        uint32_t x = valid ? key : 0u;
+    scan([&](uint32_t key, int) {
+        uint32_t x = key;
 #pragma unroll
         for (int j = 0; j < MTOP; ++j) {
             const uint32_t hi = top[j] > x ? top[j] : x;
@@ -444,50 +446,86 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     // 3. compact the survivors (any order), pad, sort descending
     if (threadIdx.x == 0) n_out = 0;
     __syncthreads();                                   // also: histogram no longer needed
-    scan([&](uint32_t key, int t, bool valid) {
-        const bool sel = valid && (key > T || (key == T && (uint32_t)t <= pos_bound));
-        const uint64_t ballot = __ballot(sel);
-        int wave_base = 0;
-        if (lane_id() == 0 && ballot) wave_base = atomicAdd(&n_out, __popcll(ballot));
-        wave_base = __shfl(wave_base, 0);
-        if (sel) {
-            const int slot = wave_base + mbcnt(ballot);
-            if (slot < nsort) sort_buf[slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
+    {
+        // one reservation per wave: count this thread's survivors, scan the counts over the wave
+        int mine = 0;
+        scan([&](uint32_t key, int t) {
+            mine += (key > T || (key == T && (uint32_t)t <= pos_bound)) ? 1 : 0;
+        });
+        int inc = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int nb = __shfl_up(inc, o);
+            if (lane_id() >= o) inc += nb;
         }
-    });
+        int wave_base = 0;
+        if (lane_id() == 63) wave_base = atomicAdd(&n_out, inc);
+        int slot = __shfl(wave_base, 63) + inc - mine;
+        scan([&](uint32_t key, int t) {
+            if (key > T || (key == T && (uint32_t)t <= pos_bound)) {
+                if (slot < NSORT) sort_buf[slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
+                ++slot;
+            }
+        });
+    }
     __syncthreads();
     CUSA_TRACE_POINT(5);
-    for (int i = k_eff + threadIdx.x; i < nsort; i += SEL_THREADS) sort_buf[i] = 0;
+    for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
-    // Bitonic network.  Wave w owns the aligned block of nsort/16 elements [w*blk, (w+1)*blk): a
-    // step whose stride is below blk pairs elements of one block only, so it needs no workgroup
-    // barrier -- a wave's LDS accesses are performed in program order -- and only the few steps
-    // with larger strides synchronise the workgroup.
+    // Bitonic network over NSORT = MTOP * 1024 composites, MTOP per thread in registers:
+    // element j of thread (wave, lane) is index wave*64*MTOP + j*64 + lane.  A step with
+    // stride < 64 exchanges between lanes of a wave, a stride of 64 .. 32*MTOP between the
+    // thread's own registers, and only larger strides go through LDS with workgroup barriers.
     {
-        const int blk = nsort / SEL_WAVES, w = wave_id(), lane = lane_id();
-        for (int size = 2; size <= nsort; size <<= 1) {
+        const int lane = lane_id(), base = wave_id() * 64 * MTOP + lane;
+        uint64_t v[MTOP];
+#pragma unroll
+        for (int j = 0; j < MTOP; ++j) v[j] = sort_buf[base + j * 64];
+#pragma unroll
+        for (int size = 2; size <= NSORT; size <<= 1) {
+#pragma unroll
             for (int stride = size >> 1; stride > 0; stride >>= 1) {
-                const bool local = stride < blk;
-                if (!local) __syncthreads();
-                for (int p = w * (blk >> 1) + lane; p < (w + 1) * (blk >> 1); p += 64) {
-                    const int lo = ((p & ~(stride - 1)) << 1) | (p & (stride - 1));
-                    const int hi = lo + stride;
-                    const uint64_t a = sort_buf[lo], c = sort_buf[hi];
-                    const bool desc = (lo & size) == 0;
-                    if ((a < c) == desc) {
-                        sort_buf[lo] = c;
-                        sort_buf[hi] = a;
-                    }
-                }
-                if (!local) {
+                if (stride >= 64 * MTOP) {             // partner in another wave
                     __syncthreads();
-                } else {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                    for (int j = 0; j < MTOP; ++j) sort_buf[base + j * 64] = v[j];
+                    __syncthreads();
+#pragma unroll
+                    for (int j = 0; j < MTOP; ++j) {
+                        const int i = base + j * 64;
+                        const uint64_t o = sort_buf[i ^ stride];
+                        const bool keep_max = ((i & stride) == 0) == ((i & size) == 0);
+                        v[j] = ((v[j] > o) == keep_max) ? v[j] : o;
+                    }
+                } else if (stride >= 64) {             // partner in this thread's registers
+                    const int js = stride >> 6;
+#pragma unroll
+                    for (int j = 0; j < MTOP; ++j) {
+                        if ((j & js) == 0 && (j | js) < MTOP) {
+                            const int i = base + j * 64;
+                            const bool desc = (i & size) == 0;
+                            const uint64_t a = v[j], c = v[j | js];
+                            const bool sw = (a < c) == desc;
+                            v[j] = sw ? c : a;
+                            v[j | js] = sw ? a : c;
+                        }
+                    }
+                } else {                               // partner in another lane of this wave
+#pragma unroll
+                    for (int j = 0; j < MTOP; ++j) {
+                        const int i = base + j * 64;
+                        const uint32_t olo = __shfl_xor((uint32_t)v[j], stride);
+                        const uint32_t ohi = __shfl_xor((uint32_t)(v[j] >> 32), stride);
+                        const uint64_t o = ((uint64_t)ohi << 32) | olo;
+                        const bool keep_max = ((i & stride) == 0) == ((i & size) == 0);
+                        v[j] = ((v[j] > o) == keep_max) ? v[j] : o;
+                    }
                 }
             }
         }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < MTOP; ++j) sort_buf[base + j * 64] = v[j];
         __syncthreads();
     }
 
