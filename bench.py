@@ -161,8 +161,12 @@ def main():
                 k["frac_of_hbm_peak"] = round(k["achieved_GBs"] / HBM_PEAK_GBS, 4)
             kernels[name] = k
         hot = max((n for n in kernels if "achieved_GBs" in kernels[n]), key=lambda n: kernels[n]["us_per_step"])
+        traffic = None                            # HBM bytes per launch from rocprofv3 counters, if a summary is committed
+        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch", {}).get(hot)
         roofline = {"kernel": hot, "bound": "hbm", "achieved": kernels[hot]["achieved_GBs"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": kernels[hot]["frac_of_hbm_peak"], "traffic": None,
+                    "unit": "GB/s", "frac": kernels[hot]["frac_of_hbm_peak"], "traffic": traffic,
                     "bytes_per_launch": kernels[hot]["bytes_per_launch"], "avg_us": kernels[hot]["avg_us"]}
 
     sb = acc.step_bytes(sched, lens, w.n_kv_heads, w.budget, w.window)
