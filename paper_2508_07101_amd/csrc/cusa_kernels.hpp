@@ -259,7 +259,7 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 //   4. ranks are written rank-major: rho_head[b][j][h].
 // With ITEMS > 0 a thread keeps its ITEMS candidates (positions i*1024 + tid) in
 // registers, loaded once with independent loads; ITEMS == 0 re-reads the scores from
-// memory in every pass, eight independent loads at a time (any length).
+// memory in every pass, 32 independent loads at a time (any length).
 
 struct SelectState {
     uint32_t prefix;     // digits fixed so far
@@ -375,18 +375,16 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
                 f(keys[i], i * SEL_THREADS + (int)threadIdx.x);
             }
         } else {
-            for (int t0 = 0; t0 < Lc; t0 += 8 * SEL_THREADS) {
-                uint32_t kk[8];
+            for (int t0 = 0; t0 < Lc; t0 += 32 * SEL_THREADS) {
+                uint32_t kk[32];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 32; ++u) {
                     const int t = t0 + u * SEL_THREADS + threadIdx.x;
                     const uint32_t kv_ = score_key(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
                     kk[u] = t < Lc ? kv_ : 0u;
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    f(kk[u], t0 + u * SEL_THREADS + (int)threadIdx.x);
-                }
+                for (int u = 0; u < 32; ++u) f(kk[u], t0 + u * SEL_THREADS + (int)threadIdx.x);
             }
         }
     };
@@ -548,6 +546,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 // window {L-W .. L-1}.
 // The table lives in LDS when the candidate range fits (LDS_TABLE), otherwise in
 // the workspace.  Every loop issues eight independent loads before it consumes them.
+// Entries of slots past the cut chunk are never written, which is harmless: they would all be
+// larger than s*.
 
 __device__ __forceinline__ int ld_relaxed(const int32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -581,77 +581,97 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 
     auto tbl_set = [&](int t, int v) { if constexpr (LDS_TABLE) lds_first[t] = v; else gfirst[t] = v; };
     auto tbl_min = [&](int t, int v) { if constexpr (LDS_TABLE) atomicMin(&lds_first[t], v); else atomicMin(&gfirst[t], v); };
-    auto tbl_get = [&](int t) { if constexpr (LDS_TABLE) return lds_first[t]; else return ld_relaxed(&gfirst[t]); };
+    // global table: the fence after each atomic-min pass also drops this CU's cached lines
+    auto tbl_get = [&](int t) { if constexpr (LDS_TABLE) return lds_first[t]; else return gfirst[t]; };
 
+    CUSA_TRACE_POINT(0);
     for (int t = tid; t < Lc; t += SEL_THREADS) tbl_set(t, 0x7fffffff);
+    if (tid == 0) s_star = -1;
     if (!LDS_TABLE) __threadfence();
     __syncthreads();
-    for (int s0 = 0; s0 < S; s0 += UNION_UNROLL * SEL_THREADS) {
+    CUSA_TRACE_POINT(1);
+
+    // Slots are taken in chunks of 8192 in slot order.  After a chunk's atomic-min pass, a slot of
+    // the chunk is a first occurrence iff first[rho[s]] == s (earlier chunks hold smaller slots
+    // and would have won), so the running count of distinct tokens is exact chunk by chunk and
+    // the walk stops at the chunk in which it reaches K-W: later slots cannot matter.
+    constexpr int CH = UNION_UNROLL * SEL_THREADS;
+    int cum = 0;                                      // first occurrences before the current chunk
+    int n_take = 0;
+    int cut_chunk = -1;
+    for (int c0 = 0; c0 < S && n_hist > 0; c0 += CH) {
         int tok[UNION_UNROLL];
 #pragma unroll
         for (int u = 0; u < UNION_UNROLL; ++u) {
-            const int s = s0 + u * SEL_THREADS + tid;
+            const int s = c0 + u * SEL_THREADS + tid;
             const int v = rho[s < S ? s : S - 1];                         // clamped: loads stay unconditional
-            tok[u] = s < S ? v : -1;
+            tok[u] = (s < S && (uint32_t)v < (uint32_t)Lc) ? v : -1;       // a pick is always a candidate position
         }
+#pragma unroll
+        for (int u = 0; u < UNION_UNROLL; ++u)
+            if (tok[u] >= 0) tbl_min(tok[u], c0 + u * SEL_THREADS + tid);
+        if (!LDS_TABLE) __threadfence();
+        __syncthreads();
+        int mine = 0;
 #pragma unroll
         for (int u = 0; u < UNION_UNROLL; ++u) {
-            const int s = s0 + u * SEL_THREADS + tid;
-            if ((uint32_t)tok[u] < (uint32_t)Lc) tbl_min(tok[u], s);   // a pick is always a candidate position
+            const int v = tbl_get(tok[u] >= 0 ? tok[u] : 0);
+            mine += (tok[u] >= 0 && v == c0 + u * SEL_THREADS + tid) ? 1 : 0;
         }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+        if (lane == 0) wave_cnt[w] = mine;
+        __syncthreads();
+        int chunk_cnt = 0;
+        for (int i = 0; i < SEL_WAVES; ++i) chunk_cnt += wave_cnt[i];
+        __syncthreads();                              // wave_cnt is reused
+        if (cum + chunk_cnt >= n_hist) {
+            cut_chunk = c0;
+            n_take = n_hist;
+            break;
+        }
+        cum += chunk_cnt;
+        n_take = cum;                                 // fewer than K-W distinct picks in total (k < K-W only)
     }
-    if (!LDS_TABLE) __threadfence();
-    __syncthreads();
+    CUSA_TRACE_POINT(2);
 
-    // cut slot: each wave owns a contiguous run of slots, walked 64 at a time; `visit`
-    // hands every 64-slot group's first-occurrence ballot to f(s0, ballot)
-    const int seg = ((S + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
-    const int s_lo = w * seg, s_hi = (s_lo + seg < S) ? s_lo + seg : S;
-    auto visit_slots = [&](auto f) {
-        for (int g0 = s_lo; g0 < s_hi; g0 += 64 * UNION_UNROLL) {
-            int tok[UNION_UNROLL], fs[UNION_UNROLL];
+    // the cut slot inside the cut chunk: each wave owns 512 consecutive slots of it
+    if (cut_chunk >= 0) {
+        constexpr int SEG = CH / SEL_WAVES;
+        const int s_lo = cut_chunk + w * SEG;
+        const int s_hi = (s_lo + SEG < S) ? s_lo + SEG : S;
+        uint64_t ballots[SEG / 64];
+        int mine = 0;
 #pragma unroll
-            for (int u = 0; u < UNION_UNROLL; ++u) {
-                const int s = g0 + u * 64 + lane;
-                const int v = rho[s < s_hi ? s : S - 1];
-                tok[u] = s < s_hi ? v : -1;
-            }
+        for (int u = 0; u < SEG / 64; ++u) {
+            const int s = s_lo + u * 64 + lane;
+            const int v = rho[s < S ? s : S - 1];
+            const bool ok = s < s_hi && (uint32_t)v < (uint32_t)Lc;
+            const int f = tbl_get(ok ? v : 0);
+            ballots[u] = __ballot(ok && f == s);
+            mine += __popcll(ballots[u]);
+        }
+        if (lane == 0) wave_cnt[w] = mine;
+        __syncthreads();
+        int before = cum;
+        for (int i = 0; i < w; ++i) before += wave_cnt[i];
+        if (before < n_hist && n_hist <= before + mine) {
+            int run = before;
 #pragma unroll
-            for (int u = 0; u < UNION_UNROLL; ++u) {
-                const bool ok = (uint32_t)tok[u] < (uint32_t)Lc;
-                const int v = tbl_get(ok ? tok[u] : 0);
-                fs[u] = ok ? v : -1;
-            }
-#pragma unroll
-            for (int u = 0; u < UNION_UNROLL; ++u) {
-                const int s = g0 + u * 64 + lane;
-                f(g0 + u * 64, __ballot(s < s_hi && fs[u] == s));
+            for (int u = 0; u < SEG / 64; ++u) {
+                const int c = __popcll(ballots[u]);
+                if (run < n_hist && n_hist <= run + c) {
+                    if (((ballots[u] >> lane) & 1) && run + mbcnt(ballots[u]) + 1 == n_hist) s_star = s_lo + u * 64 + lane;
+                }
+                run += c;
             }
         }
-    };
-    int mine = 0;
-    visit_slots([&](int, uint64_t ballot) { mine += __popcll(ballot); });
-    if (lane == 0) wave_cnt[w] = mine;
-    if (tid == 0) s_star = -1;
-    __syncthreads();
-    int before = 0, total = 0;
-    for (int i = 0; i < SEL_WAVES; ++i) {
-        if (i < w) before += wave_cnt[i];
-        total += wave_cnt[i];
-    }
-    const int n_take = n_hist < total ? n_hist : total;   // == n_hist whenever k >= K-W
-    if (n_take > 0 && before < n_take && n_take <= before + mine) {
-        int run = before;
-        visit_slots([&](int g, uint64_t ballot) {
-            const int c = __popcll(ballot);
-            if (run < n_take && n_take <= run + c) {
-                if (((ballot >> lane) & 1) && run + mbcnt(ballot) + 1 == n_take) s_star = g + lane;
-            }
-            run += c;
-        });
+    } else if (tid == 0) {
+        s_star = 0x7ffffffe;                          // every pick is kept
     }
     __syncthreads();
-    const int cut = s_star;
+    const int cut = n_take > 0 ? s_star : -1;
+    CUSA_TRACE_POINT(3);
 
     // ascending emission: each wave owns a contiguous run of positions
     const int pseg = ((Lc + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
@@ -681,6 +701,7 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         if (((ballot >> lane) & 1) && slot < n_hist) out[slot] = g + lane;
         off += __popcll(ballot);
     });
+    CUSA_TRACE_POINT(4);
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;
 }
