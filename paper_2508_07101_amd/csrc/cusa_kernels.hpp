@@ -759,6 +759,8 @@ __host__ __device__ inline int attn_active_splits(int n, int chunk) {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ int wave_base_of(unsigned tid) { return (int)(tid >> 6); }
+
 // LDS written by some lanes of a wave and read by others of the same wave: a wave's LDS
 // accesses are performed in program order, so only the compiler has to be kept from
 // reordering them.
@@ -777,12 +779,16 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
     constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
-    __shared__ float sm_acc[ATTN_WAVES][GQ][D];
+    // One buffer serves the K tiles during the loop and the 16 partial accumulators (4 waves x
+    // 4 row groups) of the final merge.
+    constexpr int KT_BYTES = ATTN_WAVES * TILE * 256, MG_BYTES = ATTN_WAVES * 4 * GQ * D * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[KT_BYTES > MG_BYTES ? KT_BYTES : MG_BYTES];
+    u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
+    float* const sm_acc = reinterpret_cast<float*>(smem_raw);            // [wave*4 + r][GQ][D] after the loop
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
-    __shared__ u32x4 ktile[ATTN_WAVES][TILE * 16];    // a wave's K rows, chunk c of row r at slot c ^ (r & 7)
     __shared__ f32x4 pbuf[ATTN_WAVES][TILE][SETS];    // a wave's softmax numerators, by token
-    __shared__ __attribute__((aligned(16))) uint16_t qlds[SETS * 4 * QSB];
+    __shared__ __attribute__((aligned(16))) uint16_t qlds_all[ATTN_WAVES][SETS * 4 * QSB];   // a private copy of q per wave
 
     CUSA_TRACE_POINT(0);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -796,11 +802,18 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
     const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
 
-    for (int i = tid; i < SETS * 4 * D; i += ATTN_THREADS) {
-        const int h = i >> 7, col = i & (D - 1);
-        qlds[h * QSB + col] = h < GQ ? q[(head0 + h) * D + col] : (uint16_t)0;   // heads beyond GQ score zero
+    // Every wave keeps its own bf16 copy of q in LDS (no workgroup barrier on the way in): lane l
+    // fetches 16 bytes of head l / 16 per set now and parks them once the first tile's loads are
+    // under way.  Heads beyond GQ score zero.
+    uint16_t* const qlds = qlds_all[wave];
+    u32x4 qv[SETS];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const int h = s * 4 + r;
+        qv[s] = *reinterpret_cast<const u32x4*>(q + (head0 + (h < GQ ? h : 0)) * D + c * 8);
+        if (h >= GQ) qv[s] = u32x4{0u, 0u, 0u, 0u};
     }
-    __syncthreads();
+    bool q_parked = false;
 
     // Scores come from V_MFMA_F32_4X4X4_16B_BF16: per lane four bf16 of q (head = lane % 4)
     // and four of K (the lane's token); after 32 instructions lane t holds q_h . k_t for the
@@ -839,10 +852,15 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
         }
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
+        if (!q_parked) {
+#pragma unroll
+            for (int s = 0; s < SETS; ++s) *reinterpret_cast<u32x4*>(&qlds[(s * 4 + r) * QSB + c * 8]) = qv[s];
+            q_parked = true;
+        }
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
             const int row = i * 4 + r;
-            ktile[wave][row * 16 + (c ^ (row & 7))] = kreg[i];
+            ktile[row * 16 + (c ^ (row & 7))] = kreg[i];
         }
         wave_lds_sync();
 
@@ -851,7 +869,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         for (int s = 0; s < SETS; ++s) sc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int cc = 0; cc < 16; ++cc) {
-            const u32x4 kw = ktile[wave][tl * 16 + (cc ^ (tl & 7))];
+            const u32x4 kw = ktile[tl * 16 + (cc ^ (tl & 7))];
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const uint2 kb = half == 0 ? make_uint2(kw.x, kw.y) : make_uint2(kw.z, kw.w);
@@ -901,21 +919,16 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     }
 
     CUSA_TRACE_POINT(1);
-    // merge the wave's four row groups, then the four waves
+    // merge: every lane parks its 8 columns x GQ heads; 16 partial accumulators per output
+    __syncthreads();                                  // all waves are done with their K tiles
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
         l[h] = row_sum16(l[h]);
         l[h] += __shfl_xor(l[h], 16);
         l[h] += __shfl_xor(l[h], 32);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            acc[h][e] += __shfl_xor(acc[h][e], 16);
-            acc[h][e] += __shfl_xor(acc[h][e], 32);
-        }
-        if (r == 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sm_acc[wave][h][c * 8 + e] = acc[h][e];
-        }
+        float* dst = &sm_acc[(((wave * 4 + r) * GQ) + h) * D + c * 8];
+        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
+        *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
         if (lane == 0) {
             sm_m[wave][h] = m[h];
             sm_l[wave][h] = l[h];
@@ -932,7 +945,10 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         for (int wv = 0; wv < ATTN_WAVES; ++wv) {
             const float mw = sm_m[wv][h];
             const float f = (mw == -INFINITY) ? 0.0f : exp2f(mw - M);
-            A = __builtin_fmaf(sm_acc[wv][h][col], f, A);
+            float a4 = 0.0f;
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) a4 += sm_acc[(((wv * 4 + rg) * GQ) + h) * D + col];
+            A = __builtin_fmaf(a4, f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
         if (n_active == 1) {                             // this workgroup saw the whole token list
