@@ -759,6 +759,31 @@ __host__ __device__ inline int attn_active_splits(int n, int chunk) {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+// V_PERMLANE32_SWAP / V_PERMLANE16_SWAP exchange halves (rows 2,3 of a with rows 0,1 of b) or
+// odd/even 16-lane rows (rows 1,3 of a with rows 0,2 of b) of two registers.  Adding the two
+// results folds a and b over that lane bit at once: the lanes whose bit is 0 end up with the
+// sum of a, the others with the sum of b.
+__device__ __forceinline__ float fold_halves(float a, float b) {
+    const auto s = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(s[0]) + __uint_as_float(s[1]);
+}
+__device__ __forceinline__ float fold_rows(float a, float b) {
+    const auto s = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(s[0]) + __uint_as_float(s[1]);
+}
+// max of a lane's value and the one 16 (32) lanes away, in every lane
+__device__ __forceinline__ float max_with_row_neighbour(float v) {
+    const auto s = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(s[0]), __uint_as_float(s[1]));
+}
+__device__ __forceinline__ float max_with_other_half(float v) {
+    const auto s = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(s[0]), __uint_as_float(s[1]));
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), lane));
+}
+
 __device__ __forceinline__ int wave_base_of(unsigned tid) { return (int)(tid >> 6); }
 
 // LDS written by some lanes of a wave and read by others of the same wave: a wave's LDS
@@ -779,12 +804,11 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
     constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
-    // One buffer serves the K tiles during the loop and the 16 partial accumulators (4 waves x
-    // 4 row groups) of the final merge.
-    constexpr int KT_BYTES = ATTN_WAVES * TILE * 256, MG_BYTES = ATTN_WAVES * 4 * GQ * D * 4;
-    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[KT_BYTES > MG_BYTES ? KT_BYTES : MG_BYTES];
+    // A wave's K tile buffer (TILE rows of 256 bytes) also carries its partial accumulators
+    // (GQ x 128 floats) into the final merge.
+    static_assert(TILE * 256 >= GQ * D * 4, "the K tile buffer must hold a wave's partial accumulators");
+    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[ATTN_WAVES * TILE * 256];
     u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
-    float* const sm_acc = reinterpret_cast<float*>(smem_raw);            // [wave*4 + r][GQ][D] after the loop
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
     __shared__ f32x4 pbuf[ATTN_WAVES][TILE][SETS];    // a wave's softmax numerators, by token
@@ -793,14 +817,17 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     CUSA_TRACE_POINT(0);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
-    const int L = kv.seq_lens[b];
-    const int n = SPARSE ? min(cnt[b], budget) : L;
-    const int n_active = attn_active_splits(n, chunk);   // chunk is a multiple of WG_TILE
-    if (split >= n_active) return;
     const int begin = split * chunk;
-    const int end = (begin + chunk < n) ? begin + chunk : n;
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
     const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
+    // The token indices of a tile are fetched one tile ahead, the first ones before the token
+    // count is known: the row of idx has `budget` entries, so a read clamped to budget - 1 stays
+    // inside it, and entries past the count are masked below like every row past the run's end.
+    int pos_next[TI];
+    if (SPARSE) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(begin + wave * TILE + i * 4 + r, budget - 1)];
+    }
 
     // Every wave keeps its own bf16 copy of q in LDS (no workgroup barrier on the way in): lane l
     // fetches 16 bytes of head l / 16 per set now and parks them once the first tile's loads are
@@ -814,6 +841,12 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         if (h >= GQ) qv[s] = u32x4{0u, 0u, 0u, 0u};
     }
     bool q_parked = false;
+    __builtin_amdgcn_sched_barrier(0);                   // the loads above do not wait for the lengths
+    const int L = kv.seq_lens[b];
+    const int n = SPARSE ? min(cnt[b], budget) : L;
+    const int n_active = attn_active_splits(n, chunk);   // chunk is a multiple of WG_TILE
+    if (split >= n_active) return;
+    const int end = (begin + chunk < n) ? begin + chunk : n;
 
     // Scores come from V_MFMA_F32_4X4X4_16B_BF16: per lane four bf16 of q (head = lane % 4)
     // and four of K (the lane's token); after 32 instructions lane t holds q_h . k_t for the
@@ -830,26 +863,25 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     }
 
     for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
-        // Rows past the end of the run are clamped to its last token (a valid row) so that all
+        // Rows past the end of the run read some token of the sequence (a valid row) so that all
         // loads are unconditional and issue back to back; their scores are masked below.
         u32x4 kreg[TI], vreg[TI];
-        int pos[TI];
-#pragma unroll
-        for (int i = 0; i < TI; ++i) {
-            const int ti = min(t0 + i * 4 + r, end - 1);
-            pos[i] = SPARSE ? my_idx[ti] : ti;
-        }
-        if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // all index loads first
         int64_t off[TI];
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
-            if (SPARSE) pos[i] = min(max(pos[i], 0), L - 1);   // an index outside the sequence is a caller error; never fault on it
-            off[i] = row_offset<PAGED>(kv, b, kvh, pos[i]) + c * 8;
+            // an index outside the sequence is a caller error; never fault on it
+            const int pos = SPARSE ? min(max(pos_next[i], 0), L - 1) : min(t0 + i * 4 + r, end - 1);
+            off[i] = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
         }
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
             kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
             vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+        }
+        if (SPARSE) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(t0 + WG_TILE + i * 4 + r, budget - 1)];
         }
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         if (!q_parked) {
@@ -886,9 +918,9 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
 #pragma unroll
         for (int h = 0; h < GQ; ++h) {
             const float z = valid ? sc[h >> 2][h & 3] * scale_log2e : -INFINITY;
-            float mt = row_max16(z);
-            mt = fmaxf(mt, __shfl_xor(mt, 16));
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            float mt = row_max16(z);                  // lanes TILE apart hold the same token
+            if (TILE > 16) mt = max_with_row_neighbour(mt);
+            if (TILE > 32) mt = max_with_other_half(mt);
             const float m_new = fmaxf(m[h], mt);      // finite: token t0 of this tile is valid
             corr[h] = exp2f(m[h] - m_new);
             m[h] = m_new;
@@ -919,22 +951,42 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     }
 
     CUSA_TRACE_POINT(1);
-    // merge: every lane parks its 8 columns x GQ heads; 16 partial accumulators per output
-    __syncthreads();                                  // all waves are done with their K tiles
+    // Merge.  Inside the wave the four row groups are folded with lane swaps: of the N = 8 GQ
+    // values of a lane, two folds leave N / 4 complete sums, those with flat index (head * 8 +
+    // column) v0 .. v0 + N/4 - 1 where v0 depends on the row group.  The wave parks them in its
+    // own tile buffer and the four waves meet in LDS.
+    constexpr int N = GQ * 8;
+    float* const wsum = reinterpret_cast<float*>(ktile);           // [GQ][D] of this wave
+    {
+        float y[N / 2], z[N / 4];
+#pragma unroll
+        for (int v = 0; v < N / 2; ++v) y[v] = fold_halves(acc[v >> 3][v & 7], acc[(v + N / 2) >> 3][(v + N / 2) & 7]);
+#pragma unroll
+        for (int v = 0; v < N / 4; ++v) z[v] = fold_rows(y[v], y[v + N / 4]);
+        const int v0 = (r >> 1) * (N / 2) + (r & 1) * (N / 4);
+        if (N / 4 >= 4) {
+#pragma unroll
+            for (int j = 0; j < N / 16; ++j) {
+                const int v = v0 + 4 * j;
+                *reinterpret_cast<f32x4*>(&wsum[(v >> 3) * D + c * 8 + (v & 7)]) = f32x4{z[4 * j], z[4 * j + 1], z[4 * j + 2], z[4 * j + 3]};
+            }
+        } else {
+            *reinterpret_cast<f32x2*>(&wsum[c * 8 + v0]) = f32x2{z[0], z[1]};
+        }
+    }
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
-        l[h] = row_sum16(l[h]);
-        l[h] += __shfl_xor(l[h], 16);
-        l[h] += __shfl_xor(l[h], 32);
-        float* dst = &sm_acc[(((wave * 4 + r) * GQ) + h) * D + c * 8];
-        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
-        *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+        float ls = row_sum16(l[h]);                      // only lanes below TILE carry a sum
+        float lt = lane_value(ls, 0);
+        if (TILE > 16) lt += lane_value(ls, 16);
+        if (TILE > 32) lt += lane_value(ls, 32) + lane_value(ls, 48);
         if (lane == 0) {
             sm_m[wave][h] = m[h];
-            sm_l[wave][h] = l[h];
+            sm_l[wave][h] = lt;
         }
     }
     __syncthreads();
+    const float* const sums = reinterpret_cast<const float*>(smem_raw);
     for (int o = tid; o < GQ * D; o += ATTN_THREADS) {
         const int h = o / D, col = o % D;
         float M = sm_m[0][h];
@@ -945,10 +997,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         for (int wv = 0; wv < ATTN_WAVES; ++wv) {
             const float mw = sm_m[wv][h];
             const float f = (mw == -INFINITY) ? 0.0f : exp2f(mw - M);
-            float a4 = 0.0f;
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) a4 += sm_acc[(((wv * 4 + rg) * GQ) + h) * D + col];
-            A = __builtin_fmaf(a4, f, A);
+            A = __builtin_fmaf(sums[wv * (TILE * 64) + o], f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
         if (n_active == 1) {                             // this workgroup saw the whole token list
@@ -977,21 +1026,34 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
     __shared__ float red_a[8][D];
     __shared__ float red_m[8], red_l[8];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, c4 = tid & 31, sr = tid >> 5;
-    const int n_splits = attn_active_splits(min(n_tok[b], n_clip), chunk);
-    if (n_splits <= 1) return;                           // the attention kernel wrote the result itself
     const int64_t base = ((int64_t)b * H + h) * stride_splits;
     constexpr int U = 4;
+    // The first batch of partials is requested before the token count is known (any of the
+    // stride_splits slots may be read); what lies beyond the active splits is dropped by select,
+    // never by a multiplication, because those slots hold whatever was there before.
+    f32x4 va[U];
+    f32x2 vml[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int sv = sr + 8 * u;
+        const int64_t p = base + (sv < stride_splits ? sv : 0);
+        va[u] = *reinterpret_cast<const f32x4*>(&part_acc[p * D + c4 * 4]);
+        vml[u] = *reinterpret_cast<const f32x2*>(&part_ml[p * 2]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const int n_splits = attn_active_splits(min(n_tok[b], n_clip), chunk);
+    if (n_splits <= 1) return;                           // the attention kernel wrote the result itself
     float mo = -INFINITY, lo = 0.0f;
     f32x4 ao = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int s0 = sr; s0 < n_splits; s0 += 8 * U) {
-        f32x4 va[U];
-        f32x2 vml[U];
+        if (s0 != sr) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int sv = s0 + 8 * u;
-            const int64_t p = base + (sv < n_splits ? sv : s0);
-            va[u] = *reinterpret_cast<const f32x4*>(&part_acc[p * D + c4 * 4]);
-            vml[u] = *reinterpret_cast<const f32x2*>(&part_ml[p * 2]);
+            for (int u = 0; u < U; ++u) {
+                const int sv = s0 + 8 * u;
+                const int64_t p = base + (sv < n_splits ? sv : s0);
+                va[u] = *reinterpret_cast<const f32x4*>(&part_acc[p * D + c4 * 4]);
+                vml[u] = *reinterpret_cast<const f32x2*>(&part_ml[p * 2]);
+            }
         }
         float mb = mo;
 #pragma unroll
@@ -1004,9 +1066,11 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float mu = vml[u].x;
-            const float f = (s0 + 8 * u < n_splits && mu != -INFINITY) ? exp2f(mu - mb) : 0.0f;
-            ao += va[u] * f;
-            lo = __builtin_fmaf(vml[u].y, f, lo);
+            const bool live = s0 + 8 * u < n_splits && mu != -INFINITY;
+            const float f = live ? exp2f(mu - mb) : 0.0f;
+            const f32x4 a = live ? va[u] : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            ao += a * f;
+            lo = __builtin_fmaf(live ? vml[u].y : 0.0f, f, lo);
         }
         mo = mb;
     }
