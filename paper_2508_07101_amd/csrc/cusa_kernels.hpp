@@ -841,11 +841,17 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         if (h >= GQ) qv[s] = u32x4{0u, 0u, 0u, 0u};
     }
     bool q_parked = false;
-    __builtin_amdgcn_sched_barrier(0);                   // the loads above do not wait for the lengths
     const int L = kv.seq_lens[b];
     const int n = SPARSE ? min(cnt[b], budget) : L;
-    const int n_active = attn_active_splits(n, chunk);   // chunk is a multiple of WG_TILE
-    if (split >= n_active) return;
+    // Everything the first tile's addresses depend on is requested above and has to be here
+    // before the first branch; otherwise the compiler sinks each load behind the branch that
+    // precedes its first use and the kernel starts with a chain of dependent memory round trips.
+    asm volatile("" ::"s"(L), "s"(n), "s"(kv.k), "s"(H));
+    if (SPARSE) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i) asm volatile("" ::"v"(pos_next[i]));
+    }
+    if (split > 0 && begin >= n) return;                 // split >= attn_active_splits(n, chunk)
     const int end = (begin + chunk < n) ? begin + chunk : n;
 
     // Scores come from V_MFMA_F32_4X4X4_16B_BF16: per lane four bf16 of q (head = lane % 4)
@@ -1000,7 +1006,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             A = __builtin_fmaf(sums[wv * (TILE * 64) + o], f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
-        if (n_active == 1) {                             // this workgroup saw the whole token list
+        if (n <= chunk) {                                // this workgroup saw the whole token list
             out[(head0 + h) * D + col] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
         } else {
             const int64_t p = (head0 + h) * n_splits + split;
@@ -1040,8 +1046,11 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
         va[u] = *reinterpret_cast<const f32x4*>(&part_acc[p * D + c4 * 4]);
         vml[u] = *reinterpret_cast<const f32x2*>(&part_ml[p * 2]);
     }
-    __builtin_amdgcn_sched_barrier(0);
     const int n_splits = attn_active_splits(min(n_tok[b], n_clip), chunk);
+    // keep the requests above the branch (the compiler would sink them behind it)
+    asm volatile("" ::"s"(n_splits));
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" ::"v"(va[u]), "v"(vml[u]));
     if (n_splits <= 1) return;                           // the attention kernel wrote the result itself
     float mo = -INFINITY, lo = 0.0f;
     f32x4 ao = {0.0f, 0.0f, 0.0f, 0.0f};
