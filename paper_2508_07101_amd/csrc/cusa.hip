@@ -4,6 +4,7 @@
 #include "../../include/cusa.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <mutex>
 #include <utility>
@@ -21,23 +22,18 @@ enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPAR
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel"};
 
-// One HIP event is recorded after every kernel; a kernel's duration is the time from the
-// event that follows the previous kernel on the same stream to the event that follows it (a
-// separate start event is recorded only for the first kernel after a reset or a stream
-// change).  Sharing events keeps the measurement's own cost per launch low, so the figures
-// stay close to a kernel trace's.
+// With the profiler on, every launch carries a start and a stop event that the runtime fills
+// from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
+// kernel trace reports: the figures exclude the gaps between kernels and the events' own cost.
 struct ProfRec {
     int id;
     hipEvent_t start, stop;
-    bool owns_start;
 };
 struct Profiler {
     std::mutex mu;
     bool on = false;
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> pool;
-    hipEvent_t last_stop = nullptr;
-    hipStream_t last_stream = nullptr;
     int64_t calls[KID_COUNT] = {0};
     double ms[KID_COUNT] = {0};
 } g_prof;
@@ -53,33 +49,29 @@ hipEvent_t prof_event() {
     return e;
 }
 
-struct ProfScope {
+template <typename T>
+struct same_as { using type = T; };
+
+// Every kernel of the library is launched through here; the arguments are converted to the
+// kernel's parameter types before they are packed.
+template <typename... KArgs>
+void launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem, hipStream_t s,
+            typename same_as<KArgs>::type... args) {
+    if (!g_prof.on) {
+        kernel<<<grid, block, shmem, s>>>(args...);
+        return;
+    }
     ProfRec rec;
-    hipStream_t stream;
-    bool active;
-    ProfScope(int id, hipStream_t s) : stream(s), active(g_prof.on) {
-        if (!active) return;
+    rec.id = kid;
+    {
         std::lock_guard<std::mutex> lk(g_prof.mu);
-        rec.id = id;
-        if (g_prof.last_stop && g_prof.last_stream == stream) {
-            rec.start = g_prof.last_stop;
-            rec.owns_start = false;
-        } else {
-            rec.start = prof_event();
-            rec.owns_start = true;
-            (void)hipEventRecord(rec.start, stream);
-        }
+        rec.start = prof_event();
         rec.stop = prof_event();
     }
-    ~ProfScope() {
-        if (!active) return;
-        (void)hipEventRecord(rec.stop, stream);
-        std::lock_guard<std::mutex> lk(g_prof.mu);
-        g_prof.recs.push_back(rec);
-        g_prof.last_stop = rec.stop;
-        g_prof.last_stream = stream;
-    }
-};
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, s, rec.start, rec.stop, 0, args...);
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.recs.push_back(rec);
+}
 
 // ------------------------------------------------------------------ validation
 
@@ -229,10 +221,11 @@ template <int GQ, int TI, bool SPARSE>
 void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
                          const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
                          uint16_t* out, int n_splits, int chunk, int H) {
+    const int kid = SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL;
     if (paged)
-        attn_kernel<GQ, TI, SPARSE, true><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, true>, grid, ATTN_THREADS, 0, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
     else
-        attn_kernel<GQ, TI, SPARSE, false><<<grid, ATTN_THREADS, 0, s>>>(view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, false>, grid, ATTN_THREADS, 0, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
 }
 
 template <int GQ, bool SPARSE>
@@ -262,7 +255,6 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     uint16_t* oo = static_cast<uint16_t*>(out);
     dim3 grid(pl.n_splits, p->n_kv_heads, p->batch);
     {
-        ProfScope ps(SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL, s);
         switch (g) {
             case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
             case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
@@ -272,9 +264,8 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     }
     if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
     if (pl.n_splits > 1) {
-        ProfScope ps(KID_REDUCE, s);
-        attn_reduce_kernel<<<dim3(H, p->batch), 256, 0, s>>>(pa, pm, oo, SPARSE ? cnt : kv->seq_lens,
-                                                             SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H);
+        launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, pa, pm, oo, SPARSE ? cnt : kv->seq_lens,
+               SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H);
     }
     return launch_status();
 }
@@ -303,7 +294,7 @@ cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp,
     const size_t shmem = (size_t)MTOP * SEL_THREADS * sizeof(uint64_t);
     if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
         return CUSA_ERR_LAUNCH;
-    topk_kernel<ITEMS, MTOP><<<grid, SEL_THREADS, shmem, s>>>(P, ldp, seq_lens, rho_head, H, k, budget, window);
+    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
     return launch_status();
 }
 
@@ -321,9 +312,9 @@ template <int GQ>
 void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
                   int H, int budget, int window, int tiles_per_seq, int n_tiles) {
     if (paged)
-        score_kernel<GQ, true><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, true>, grid, 256, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
     else
-        score_kernel<GQ, false><<<grid, 256, 0, s>>>(view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, false>, grid, 256, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
 }
 
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
@@ -344,7 +335,6 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         const int n_tiles = (int)n_tiles64;
         const int grid = n_tiles < SCORE_GRID ? n_tiles : SCORE_GRID;   // two 64 KB tiles fit a CU's LDS
         {
-            ProfScope ps(KID_SCORE, s);
             switch (g) {
                 case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
                 case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
@@ -356,7 +346,6 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
         cusa_status st;
         {
-            ProfScope ps(KID_TOPK, s);
             const dim3 tg(H, B);
             if (items <= 4) st = launch_topk<4>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
             else if (items <= 8) st = launch_topk<8>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
@@ -367,17 +356,16 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         if (st != CUSA_OK) return st;
     }
     {
-        ProfScope ps(KID_UNION, s);
         const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
         const size_t table = ((size_t)lc_max * 4 + 255) & ~(size_t)255;
         bool in_lds = lc_max > 0 && table <= UNION_LDS_TABLE_MAX;
         if (in_lds && table > 48 * 1024) in_lds = allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel<true>), table);
         if (in_lds)
-            union_kernel<true><<<B, SEL_THREADS, table, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
-                                                             p->budget, p->window);
+            launch(KID_UNION, union_kernel<true>, B, SEL_THREADS, table, s, rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
+                   p->budget, p->window);
         else
-            union_kernel<false><<<B, SEL_THREADS, 0, s>>>(rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
-                                                          p->budget, p->window);
+            launch(KID_UNION, union_kernel<false>, B, SEL_THREADS, 0, s, rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
+                   p->budget, p->window);
     }
     return launch_status();
 }
@@ -510,7 +498,6 @@ const char* cusa_profile_kernel_name(int32_t id) { return (id >= 0 && id < KID_C
 void cusa_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
     g_prof.on = on != 0;
-    g_prof.last_stop = nullptr;
 }
 
 static void prof_drain_locked() {
@@ -520,11 +507,10 @@ static void prof_drain_locked() {
             g_prof.calls[r.id] += 1;
             g_prof.ms[r.id] += ms;
         }
-        if (r.owns_start) g_prof.pool.push_back(r.start);
+        g_prof.pool.push_back(r.start);
         g_prof.pool.push_back(r.stop);
     }
     g_prof.recs.clear();
-    g_prof.last_stop = nullptr;
 }
 
 void cusa_profile_reset(void) {
