@@ -291,7 +291,7 @@ bool allow_dynamic_lds(const void* fn, size_t bytes) {
 template <int ITEMS, int MTOP>
 cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
                           int32_t* rho_head, int H, int k, int budget, int window) {
-    const size_t shmem = (size_t)MTOP * SEL_THREADS * sizeof(uint64_t);
+    const size_t shmem = ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
     if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
         return CUSA_ERR_LAUNCH;
     launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window);

@@ -309,10 +309,11 @@ __device__ __forceinline__ void pick_digit(int* hist, int* scratch, SelectState*
 // Leaves the key in st->prefix, the number still wanted among equal keys in st->need and
 // their count in st->count_eq.
 // Keys whose top digit is below min_digit0 are known not to matter and are not counted.
+// first_pass > 0 resumes a selection whose leading digits *st already holds.
 template <typename Scan, typename KeyMap>
-__device__ __forceinline__ void radix_select(int need, uint32_t min_digit0, Scan scan, KeyMap key_map, int* hist,
-                                             int* scratch, SelectState* st) {
-    if (threadIdx.x == 0) {
+__device__ __forceinline__ void radix_select(int first_pass, int need, uint32_t min_digit0, Scan scan, KeyMap key_map,
+                                             int* hist, int* scratch, SelectState* st) {
+    if (first_pass == 0 && threadIdx.x == 0) {
         st->prefix = 0;
         st->need = need;
         st->count_eq = 0;
@@ -320,7 +321,8 @@ __device__ __forceinline__ void radix_select(int need, uint32_t min_digit0, Scan
     const int shifts[3] = {21, 10, 0};
     const int bits[3] = {11, 11, 10};
     uint32_t mask = 0;
-    for (int pass = 0; pass < 3; ++pass) {
+    for (int pass = 0; pass < first_pass; ++pass) mask |= ((1u << bits[pass]) - 1u) << shifts[pass];
+    for (int pass = first_pass; pass < 3; ++pass) {
         for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
         __syncthreads();
         const uint32_t prefix = st->prefix;
@@ -339,16 +341,39 @@ __device__ __forceinline__ void radix_select(int need, uint32_t min_digit0, Scan
     }
 }
 
+// Adds this thread's count to a workgroup counter with one LDS atomic per wave; returns the first of
+// the thread's slots.  The counter must be zero and visible before, and is complete after the next
+// workgroup barrier.
+__device__ __forceinline__ int wave_reserve(int mine, int* counter) {
+    int inc = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int nb = __shfl_up(inc, o);
+        if (lane_id() >= o) inc += nb;
+    }
+    int wave_base = 0;
+    if (lane_id() == 63) wave_base = atomicAdd(counter, inc);
+    return __shfl(wave_base, 63) + inc - mine;
+}
+
+// Entries of the LDS candidate list of topk_kernel<ITEMS, MTOP> (0: no list; short rows are
+// cheap to walk again).
+__host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
+    return (items != 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
+}
+
 template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
                                                             int budget, int window) {
     constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
-    extern __shared__ uint64_t sort_buf[];            // NSORT composites; aliases the histogram
+    constexpr int CAP = topk_list_cap(ITEMS, MTOP);
+    extern __shared__ uint64_t sort_buf[];            // NSORT composites (aliases the histogram), then CAP list entries
+    uint64_t* const cand = sort_buf + NSORT;
     __shared__ int scratch[SEL_WAVES + 1];
     __shared__ SelectState st;
-    __shared__ int n_out;
+    __shared__ int n_out, n_list;
     int* hist = reinterpret_cast<int*>(sort_buf);     // 2048 ints = 8 KB <= NSORT * 8
 
     const int h = blockIdx.x, b = blockIdx.y;
@@ -422,51 +447,87 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     __syncthreads();
 
     CUSA_TRACE_POINT(2);
-    // 1. score key of the k_eff-th best
-    radix_select(k_eff, d0, scan, [](uint32_t skey, int, uint32_t* key) { *key = skey; return true; },
-                 hist, scratch, &st);
-    const uint32_t T = st.prefix;
-    const int need_eq = st.need, count_eq = st.count_eq;
-    __syncthreads();
-
-    CUSA_TRACE_POINT(3);
-    // 2. position bound among the ties (rare: only when ties straddle the cut)
-    uint32_t pos_bound = 0xffffffffu;                  // take every tie
-    if (count_eq > need_eq) {
-        radix_select(need_eq, 0u, scan,
-                     [T](uint32_t skey, int t, uint32_t* key) { *key = ~(uint32_t)t; return skey == T; },
+    // 1-3 for candidates delivered by scan_fn: the remaining digits of the k_eff-th best score key
+    // T (its top digit is already in st), the position bound among the keys equal to T when they
+    // straddle the cut (rare), and the survivors' composites compacted into sort_buf in any order.
+    auto finish = [&](auto scan_fn) {
+        radix_select(1, k_eff, 0u, scan_fn, [](uint32_t skey, int, uint32_t* key) { *key = skey; return true; },
                      hist, scratch, &st);
-        pos_bound = ~st.prefix;                        // need_eq-th smallest tying position
+        const uint32_t T = st.prefix;
+        const int need_eq = st.need, count_eq = st.count_eq;
         __syncthreads();
-    }
-
-    CUSA_TRACE_POINT(4);
-    // 3. compact the survivors (any order), pad, sort descending
-    if (threadIdx.x == 0) n_out = 0;
-    __syncthreads();                                   // also: histogram no longer needed
-    {
+        CUSA_TRACE_POINT(3);
+        uint32_t pos_bound = 0xffffffffu;              // take every tie
+        if (count_eq > need_eq) {
+            radix_select(0, need_eq, 0u, scan_fn,
+                         [T](uint32_t skey, int t, uint32_t* key) { *key = ~(uint32_t)t; return skey == T; },
+                         hist, scratch, &st);
+            pos_bound = ~st.prefix;                    // need_eq-th smallest tying position
+            __syncthreads();
+        }
+        CUSA_TRACE_POINT(4);
+        if (threadIdx.x == 0) n_out = 0;
+        __syncthreads();                               // also: histogram no longer needed
         // one reservation per wave: count this thread's survivors, scan the counts over the wave
         int mine = 0;
-        scan([&](uint32_t key, int t) {
+        scan_fn([&](uint32_t key, int t) {
             mine += (key > T || (key == T && (uint32_t)t <= pos_bound)) ? 1 : 0;
         });
-        int inc = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int nb = __shfl_up(inc, o);
-            if (lane_id() >= o) inc += nb;
-        }
-        int wave_base = 0;
-        if (lane_id() == 63) wave_base = atomicAdd(&n_out, inc);
-        int slot = __shfl(wave_base, 63) + inc - mine;
-        scan([&](uint32_t key, int t) {
+        int slot = wave_reserve(mine, &n_out);
+        scan_fn([&](uint32_t key, int t) {
             if (key > T || (key == T && (uint32_t)t <= pos_bound)) {
                 if (slot < NSORT) sort_buf[slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
                 ++slot;
             }
         });
+        __syncthreads();
+    };
+
+    // The top digit of T comes from one histogram pass over all candidates whose top digit is at
+    // least d0.  Those are the only ones that can still matter; when they fit they are copied to
+    // an LDS list and everything after this pass walks the list (a few entries per thread)
+    // instead of every candidate again.
+    for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
+    if (threadIdx.x == 0) {
+        st.prefix = 0;
+        st.need = k_eff;
+        st.count_eq = 0;
+        n_list = 0;
     }
     __syncthreads();
+    int listable = 0;
+    scan([&](uint32_t key, int) {
+        const uint32_t dg = key >> 21;
+        if (dg >= d0) {
+            atomicAdd(&hist[dg], 1);
+            ++listable;
+        }
+    });
+    __syncthreads();
+    pick_digit<2048>(hist, scratch, &st, 21);
+    bool listed = false;
+    if constexpr (CAP > 0) {
+        int slot = wave_reserve(listable, &n_list);
+        __syncthreads();
+        listed = n_list <= CAP;
+        if (listed) {
+            scan([&](uint32_t key, int t) {
+                if ((key >> 21) >= d0) cand[slot++] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
+            });
+            __syncthreads();
+        }
+    }
+    if (listed) {
+        const int n = n_list;
+        finish([&](auto f) {
+            for (int i = threadIdx.x; i < n; i += SEL_THREADS) {
+                const uint64_t cv = cand[i];
+                f((uint32_t)(cv >> 32), (int)~(uint32_t)cv);
+            }
+        });
+    } else {
+        finish(scan);
+    }
     CUSA_TRACE_POINT(5);
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
