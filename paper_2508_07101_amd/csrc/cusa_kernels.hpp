@@ -362,6 +362,40 @@ __host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
     return (items != 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
 }
 
+// Value of lane (l ^ STRIDE) for STRIDE < 64 without the LDS crossbar: DPP moves inside a 16-lane
+// row, row/half swaps beyond.
+template <int CTRL, int BANK_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t old, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)v, CTRL, 0xF, BANK_MASK, false);
+}
+template <int STRIDE>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+    if constexpr (STRIDE == 1) return dpp_u32<0xB1>(0u, v);            // quad_perm [1,0,3,2]
+    else if constexpr (STRIDE == 2) return dpp_u32<0x4E>(0u, v);       // quad_perm [2,3,0,1]
+    else if constexpr (STRIDE == 4) {
+        const uint32_t t = dpp_u32<0x104, 0x5>(0u, v);                // row_shl:4 into lanes 0-3, 8-11 of a row
+        return dpp_u32<0x114, 0xA>(t, v);                             // row_shr:4 into lanes 4-7, 12-15
+    } else if constexpr (STRIDE == 8) return dpp_u32<0x128>(0u, v);    // row_ror:8
+    else if constexpr (STRIDE == 16) {
+        const auto s = __builtin_amdgcn_permlane16_swap(v, v, false, false);   // s[0]: rows 0,0,2,2; s[1]: rows 1,1,3,3
+        return (threadIdx.x & 16) ? s[0] : s[1];
+    } else {
+        static_assert(STRIDE == 32, "lane_xor: stride must be a power of two below 64");
+        const auto s = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // s[0]: lower half twice; s[1]: upper half twice
+        return (threadIdx.x & 32) ? s[0] : s[1];
+    }
+}
+__device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
+    switch (stride) {
+        case 1: return lane_xor<1>(v);
+        case 2: return lane_xor<2>(v);
+        case 4: return lane_xor<4>(v);
+        case 8: return lane_xor<8>(v);
+        case 16: return lane_xor<16>(v);
+        default: return lane_xor<32>(v);
+    }
+}
+
 template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
@@ -573,8 +607,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 #pragma unroll
                     for (int j = 0; j < MTOP; ++j) {
                         const int i = base + j * 64;
-                        const uint32_t olo = __shfl_xor((uint32_t)v[j], stride);
-                        const uint32_t ohi = __shfl_xor((uint32_t)(v[j] >> 32), stride);
+                        const uint32_t olo = lane_xor_any((uint32_t)v[j], stride);
+                        const uint32_t ohi = lane_xor_any((uint32_t)(v[j] >> 32), stride);
                         const uint64_t o = ((uint64_t)ohi << 32) | olo;
                         const bool keep_max = ((i & stride) == 0) == ((i & size) == 0);
                         v[j] = ((v[j] > o) == keep_max) ? v[j] : o;
