@@ -120,7 +120,8 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
  * q    device bf16 [batch][n_q_heads][128], this layer's query.
  * idx  device int32 [batch][budget]: rho ascending; entries >= cnt[b] unspecified.
  * cnt  device int32 [batch]: |rho| = min(K, L_b).
- * Errors: INVALID_ARG, UNSUPPORTED (rank_mode), WORKSPACE_TOO_SMALL, LAUNCH. */
+ * Errors: INVALID_ARG, UNSUPPORTED (rank_mode; max_seq_len - W above 1 179 648,
+ * the positions the selection's on-chip bitmap covers), WORKSPACE_TOO_SMALL, LAUNCH. */
 cusa_status cusa_select(const cusa_params* params, const void* q, const cusa_kv* kv,
                         int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream);
 

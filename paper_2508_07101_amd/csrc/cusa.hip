@@ -174,7 +174,7 @@ AttnPlan plan_attn(int n_max, int BG, int g) {
 }
 
 struct WsLayout {
-    size_t scores, rho_head, first, part_acc, part_ml, total;
+    size_t scores, rho_head, part_acc, part_ml, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -195,7 +195,6 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     size_t off = 0;
     w.scores = off;    off += align256((size_t)(B * H * w.ldp) * 4);
     w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);
-    w.first = off;     off += align256((size_t)(B * w.ldp) * 4);
     w.part_acc = off;  off += align256((size_t)(B * H * w.max_splits * D) * 4);
     w.part_ml = off;   off += align256((size_t)(B * H * w.max_splits * 2) * 4);
     w.total = off;
@@ -272,7 +271,6 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
 
 // LDS beyond 48 KB per workgroup has to be granted per kernel; remembered per kernel so the
 // runtime is asked once.
-constexpr size_t UNION_LDS_TABLE_MAX = 144 * 1024;
 
 bool allow_dynamic_lds(const void* fn, size_t bytes) {
     static std::mutex mu;
@@ -325,8 +323,8 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
     const uint16_t* qf = static_cast<const uint16_t*>(q);
     float* P = ws_ptr<float>(ws, w.scores);
     int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
-    int32_t* first = ws_ptr<int32_t>(ws, w.first);
 
+    if ((int64_t)kv->max_seq_len - p->window > UNION_MAX_POSITIONS) return CUSA_ERR_UNSUPPORTED;
     if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
         const int lc_max = kv->max_seq_len - p->window;
         const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
@@ -356,16 +354,12 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         if (st != CUSA_OK) return st;
     }
     {
+        // the union's bitmap over candidate positions lives in LDS
         const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
-        const size_t table = ((size_t)lc_max * 4 + 255) & ~(size_t)255;
-        bool in_lds = lc_max > 0 && table <= UNION_LDS_TABLE_MAX;
-        if (in_lds && table > 48 * 1024) in_lds = allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel<true>), table);
-        if (in_lds)
-            launch(KID_UNION, union_kernel<true>, B, SEL_THREADS, table, s, rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
-                   p->budget, p->window);
-        else
-            launch(KID_UNION, union_kernel<false>, B, SEL_THREADS, 0, s, rho_head, kv->seq_lens, first, w.ldp, idx, cnt, H, w.k,
-                   p->budget, p->window);
+        const size_t bitmap = ((((size_t)lc_max + 31) / 32) * 4 + 255) & ~(size_t)255;
+        if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel), bitmap)) return CUSA_ERR_LAUNCH;
+        launch(KID_UNION, union_kernel, B, SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H, w.k, p->budget,
+               p->window);
     }
     return launch_status();
 }

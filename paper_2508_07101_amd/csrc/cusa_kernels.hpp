@@ -632,33 +632,30 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 
 // ---------------------------------------------------------------- union / rank / window
 //
-// One 1024-thread workgroup per sequence.  Slot s = j*H + h of the rank-major
-// array is head h's rank-j pick; a token's global rank is the smallest slot that
-// names it.  first[t] = that slot (atomic min, order-independent); a slot is the
-// "first occurrence" of its token iff first[rho[s]] == s; the cut slot s* is the
-// one at which the count of first occurrences reaches K-W; rho's historical part
-// is {t : first[t] <= s*}, emitted in ascending position order, followed by the
+// One 1024-thread workgroup per sequence.  Slot s = j*H + h of the rank-major array is head h's
+// rank-j pick; the historical part of rho is the set of the first K-W distinct tokens met when
+// the slots are walked in order.  The set is a bitmap over the candidate positions in LDS (one bit
+// per position: 16 KB for 131072 tokens).  A range of slots is added with one atomic OR per slot;
+// the OR's return value tells whether the slot set its bit, so the number of new tokens in the
+// range is exact even though, among slots of the range that name the same token, an arbitrary
+// one sets it.  Ranges are taken in slot order, 8192 slots at a time; the range in which the
+// count would pass K-W is taken back (the bits it set are cleared) and walked again in 1024-slot
+// ranges, the crossing one of those in 64-slot groups by a single wave, and the crossing group is
+// resolved exactly: a lane's pick counts if no lower lane of the group names the same token.
+// What is left set is the answer; it is emitted in ascending position order, followed by the
 // window {L-W .. L-1}.
-// The table lives in LDS when the candidate range fits (LDS_TABLE), otherwise in
-// the workspace.  Every loop issues eight independent loads before it consumes them.
-// Entries of slots past the cut chunk are never written, which is harmless: they would all be
-// larger than s*.
-
-__device__ __forceinline__ int ld_relaxed(const int32_t* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 constexpr int UNION_UNROLL = 8;
+constexpr int UNION_MAX_POSITIONS = 144 * 1024 * 8;   // candidate positions a 144 KB bitmap covers
 
-template <bool LDS_TABLE>
 __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __restrict__ rho_head,
                                                              const int32_t* __restrict__ seq_lens,
-                                                             int32_t* first_all, int64_t ld_first,
                                                              int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
                                                              int H, int k, int budget, int window) {
-    extern __shared__ int32_t lds_first[];
-    __shared__ int wave_cnt[SEL_WAVES];
-    __shared__ int s_star;
+    extern __shared__ uint32_t bits[];                // ceil(Lc / 32) words
+    __shared__ int wave_cnt[2 * SEL_WAVES];
+    __shared__ int scratch[SEL_WAVES + 1];
+    __shared__ int picks[SEL_THREADS];                // the picks of the crossing 1024-slot range, by slot
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int L = seq_lens[b];
     int32_t* __restrict__ out = idx + (int64_t)b * budget;
@@ -671,131 +668,155 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     const int k_eff = k < Lc ? k : Lc;
     const int S = k_eff * H;
     const int n_hist = budget - window;
-    int32_t* gfirst = first_all + (int64_t)b * ld_first;
     const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
-
-    auto tbl_set = [&](int t, int v) { if constexpr (LDS_TABLE) lds_first[t] = v; else gfirst[t] = v; };
-    auto tbl_min = [&](int t, int v) { if constexpr (LDS_TABLE) atomicMin(&lds_first[t], v); else atomicMin(&gfirst[t], v); };
-    // global table: the fence after each atomic-min pass also drops this CU's cached lines
-    auto tbl_get = [&](int t) { if constexpr (LDS_TABLE) return lds_first[t]; else return gfirst[t]; };
+    const int n_words = (Lc + 31) >> 5;
 
     CUSA_TRACE_POINT(0);
-    for (int t = tid; t < Lc; t += SEL_THREADS) tbl_set(t, 0x7fffffff);
-    if (tid == 0) s_star = -1;
-    if (!LDS_TABLE) __threadfence();
+    for (int i = tid; i < n_words; i += SEL_THREADS) bits[i] = 0u;
     __syncthreads();
     CUSA_TRACE_POINT(1);
 
-    // Slots are taken in chunks of 8192 in slot order.  After a chunk's atomic-min pass, a slot of
-    // the chunk is a first occurrence iff first[rho[s]] == s (earlier chunks hold smaller slots
-    // and would have won), so the running count of distinct tokens is exact chunk by chunk and
-    // the walk stops at the chunk in which it reaches K-W: later slots cannot matter.
-    constexpr int CH = UNION_UNROLL * SEL_THREADS;
-    int cum = 0;                                      // first occurrences before the current chunk
-    int n_take = 0;
-    int cut_chunk = -1;
-    for (int c0 = 0; c0 < S && n_hist > 0; c0 += CH) {
-        int tok[UNION_UNROLL];
+    // The picks of the UNION_UNROLL slots s0 + u * 1024 + tid are requested with clamped,
+    // unconditional loads (request_picks) and looked at later (take_picks: -1 past the end; a pick is
+    // always a candidate position).  The empty asm keeps the compiler from turning the loads into one
+    // branch each.
+    auto request_picks = [&](int s0, int* raw) {
 #pragma unroll
-        for (int u = 0; u < UNION_UNROLL; ++u) {
-            const int s = c0 + u * SEL_THREADS + tid;
-            const int v = rho[s < S ? s : S - 1];                         // clamped: loads stay unconditional
-            tok[u] = (s < S && (uint32_t)v < (uint32_t)Lc) ? v : -1;       // a pick is always a candidate position
-        }
+        for (int u = 0; u < UNION_UNROLL; ++u) raw[u] = rho[min(s0 + u * SEL_THREADS + tid, S - 1)];
+    };
+    auto take_picks = [&](int s0, int* raw, int* dst) {
+#pragma unroll
+        for (int u = 0; u < UNION_UNROLL; ++u) asm volatile("" : "+v"(raw[u]));
 #pragma unroll
         for (int u = 0; u < UNION_UNROLL; ++u)
-            if (tok[u] >= 0) tbl_min(tok[u], c0 + u * SEL_THREADS + tid);
-        if (!LDS_TABLE) __threadfence();
+            dst[u] = (s0 + u * SEL_THREADS + tid < S && (uint32_t)raw[u] < (uint32_t)Lc) ? raw[u] : -1;
+    };
+    // workgroup total of per-wave counts (wave-uniform argument); wave_cnt alternates between two
+    // halves so that one barrier per call is enough
+    int parity = 0;
+    auto block_total = [&](int wave_total) {
+        int* const slot = wave_cnt + parity * SEL_WAVES;
+        parity ^= 1;
+        if (lane == 0) slot[w] = wave_total;
         __syncthreads();
-        int mine = 0;
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < SEL_WAVES; ++i) sum += slot[i];
+        return sum;
+    };
+    int cum = 0;                                       // distinct tokens in the bitmap
+    bool crossed = false;
+    constexpr int CH = UNION_UNROLL * SEL_THREADS;
+    int tok[UNION_UNROLL], raw[UNION_UNROLL];          // this range's picks; the next range's, requested early
+    request_picks(0, raw);
+    for (int c0 = 0; c0 < S && n_hist > 0; c0 += CH) {
+        take_picks(c0, raw, tok);
+        request_picks(c0 + CH, raw);
+        uint32_t won = 0;
+        int wave_added = 0;
 #pragma unroll
         for (int u = 0; u < UNION_UNROLL; ++u) {
-            const int v = tbl_get(tok[u] >= 0 ? tok[u] : 0);
-            mine += (tok[u] >= 0 && v == c0 + u * SEL_THREADS + tid) ? 1 : 0;
+            const uint32_t bit = 1u << (tok[u] & 31);
+            const uint32_t old = atomicOr(&bits[tok[u] >= 0 ? tok[u] >> 5 : 0], tok[u] >= 0 ? bit : 0u);
+            const bool wn = tok[u] >= 0 && !(old & bit);
+            if (wn) won |= 1u << u;
+            wave_added += __popcll(__ballot(wn));
         }
+        const int added = block_total(wave_added);
+        if (cum + added >= n_hist) {                   // take the range back and look closer
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-        if (lane == 0) wave_cnt[w] = mine;
-        __syncthreads();
-        int chunk_cnt = 0;
-        for (int i = 0; i < SEL_WAVES; ++i) chunk_cnt += wave_cnt[i];
-        __syncthreads();                              // wave_cnt is reused
-        if (cum + chunk_cnt >= n_hist) {
-            cut_chunk = c0;
-            n_take = n_hist;
+            for (int u = 0; u < UNION_UNROLL; ++u)
+                if ((won >> u) & 1) atomicAnd(&bits[tok[u] >> 5], ~(1u << (tok[u] & 31)));
+            __syncthreads();
+            crossed = true;
             break;
         }
-        cum += chunk_cnt;
-        n_take = cum;                                 // fewer than K-W distinct picks in total (k < K-W only)
+        cum += added;
     }
     CUSA_TRACE_POINT(2);
 
-    // the cut slot inside the cut chunk: each wave owns 512 consecutive slots of it
-    if (cut_chunk >= 0) {
-        constexpr int SEG = CH / SEL_WAVES;
-        const int s_lo = cut_chunk + w * SEG;
-        const int s_hi = (s_lo + SEG < S) ? s_lo + SEG : S;
-        uint64_t ballots[SEG / 64];
-        int mine = 0;
+    int n_take = cum;                                  // fewer than K-W distinct picks in total (k < K-W only)
+    if (crossed) {
+        // tok[u] of thread i is slot u * 1024 + i of the crossing range
+        n_take = n_hist;
+        int my_pick = -1;                              // the thread's pick in the crossing 1024-slot range
+        bool found = false;
 #pragma unroll
-        for (int u = 0; u < SEG / 64; ++u) {
-            const int s = s_lo + u * 64 + lane;
-            const int v = rho[s < S ? s : S - 1];
-            const bool ok = s < s_hi && (uint32_t)v < (uint32_t)Lc;
-            const int f = tbl_get(ok ? v : 0);
-            ballots[u] = __ballot(ok && f == s);
-            mine += __popcll(ballots[u]);
-        }
-        if (lane == 0) wave_cnt[w] = mine;
-        __syncthreads();
-        int before = cum;
-        for (int i = 0; i < w; ++i) before += wave_cnt[i];
-        if (before < n_hist && n_hist <= before + mine) {
-            int run = before;
-#pragma unroll
-            for (int u = 0; u < SEG / 64; ++u) {
-                const int c = __popcll(ballots[u]);
-                if (run < n_hist && n_hist <= run + c) {
-                    if (((ballots[u] >> lane) & 1) && run + mbcnt(ballots[u]) + 1 == n_hist) s_star = s_lo + u * 64 + lane;
+        for (int u = 0; u < UNION_UNROLL; ++u) {
+            if (!found) {                              // uniform
+                const uint32_t bit = 1u << (tok[u] & 31);
+                const uint32_t old = atomicOr(&bits[tok[u] >= 0 ? tok[u] >> 5 : 0], tok[u] >= 0 ? bit : 0u);
+                const bool won = tok[u] >= 0 && !(old & bit);
+                const int added = block_total(__popcll(__ballot(won)));
+                if (cum + added >= n_hist) {
+                    if (won) atomicAnd(&bits[tok[u] >> 5], ~bit);
+                    my_pick = tok[u];
+                    found = true;
+                } else {
+                    cum += added;
                 }
-                run += c;
             }
         }
-    } else if (tid == 0) {
-        s_star = 0x7ffffffe;                          // every pick is kept
+        picks[tid] = my_pick;
+        __syncthreads();
+        if (w == 0) {                                  // one wave: its LDS accesses happen in program order
+            int group_pick[SEL_WAVES];
+#pragma unroll
+            for (int g = 0; g < SEL_WAVES; ++g) group_pick[g] = picks[g * 64 + lane];
+            int t = -1;                                // the lane's pick in the crossing group
+            bool found = false;
+#pragma unroll
+            for (int g = 0; g < SEL_WAVES; ++g) {
+                if (!found) {                          // uniform
+                    const int tg = group_pick[g];
+                    const uint32_t bit = 1u << (tg & 31);
+                    uint32_t* const word = &bits[tg >= 0 ? tg >> 5 : 0];
+                    const bool won = tg >= 0 && !(atomicOr(word, tg >= 0 ? bit : 0u) & bit);
+                    const int c = __popcll(__ballot(won));
+                    if (cum + c < n_hist) {
+                        cum += c;
+                    } else {                           // take the group back
+                        if (won) atomicAnd(word, ~bit);
+                        t = tg;
+                        found = true;
+                    }
+                }
+            }
+            if (found) {
+                // a pick of the crossing group counts only if no lower lane names its token
+                bool dup = false;
+#pragma unroll
+                for (int l = 0; l < 63; ++l) {
+                    const int tl = __builtin_amdgcn_readlane(t, l);
+                    dup |= (l < lane) && (tl == t);
+                }
+                const uint32_t bit = 1u << (t & 31);
+                uint32_t* const word = &bits[t >= 0 ? t >> 5 : 0];
+                const bool is_new = t >= 0 && !dup && !(*word & bit);
+                const uint64_t ballot = __ballot(is_new);
+                if (is_new && cum + mbcnt(ballot) < n_hist) atomicOr(word, bit);
+            }
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    const int cut = n_take > 0 ? s_star : -1;
     CUSA_TRACE_POINT(3);
 
-    // ascending emission: each wave owns a contiguous run of positions
-    const int pseg = ((Lc + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
-    const int p_lo = w * pseg, p_hi = (p_lo + pseg < Lc) ? p_lo + pseg : Lc;
-    auto visit_pos = [&](auto f) {
-        for (int g0 = p_lo; g0 < p_hi; g0 += 64 * UNION_UNROLL) {
-            int fv[UNION_UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNION_UNROLL; ++u) {
-                const int t = g0 + u * 64 + lane;
-                const int v = tbl_get(t < p_hi ? t : Lc - 1);
-                fv[u] = t < p_hi ? v : 0x7fffffff;
-            }
-#pragma unroll
-            for (int u = 0; u < UNION_UNROLL; ++u) f(g0 + u * 64, __ballot(fv[u] <= cut));
+    // ascending emission: thread i owns the words [i * wpt, i * wpt + wpt)
+    const int wpt = (n_words + SEL_THREADS - 1) / SEL_THREADS;
+    const int w_lo = tid * wpt, w_hi = (w_lo + wpt < n_words) ? w_lo + wpt : n_words;
+    int mine = 0;
+    for (int i = w_lo; i < w_hi; ++i) mine += __popc(bits[i]);
+    int total;
+    int off = block_scan_excl(mine, scratch, &total);
+    for (int i = w_lo; i < w_hi; ++i) {
+        uint32_t word = bits[i];
+        while (word) {
+            const int bpos = __ffs(word) - 1;
+            if (off < n_hist) out[off] = i * 32 + bpos;
+            ++off;
+            word &= word - 1;
         }
-    };
-    int sel_cnt = 0;
-    visit_pos([&](int, uint64_t ballot) { sel_cnt += __popcll(ballot); });
-    __syncthreads();                                      // wave_cnt reuse
-    if (lane == 0) wave_cnt[w] = sel_cnt;
-    __syncthreads();
-    int off = 0;
-    for (int i = 0; i < w; ++i) off += wave_cnt[i];
-    visit_pos([&](int g, uint64_t ballot) {
-        const int slot = off + mbcnt(ballot);
-        if (((ballot >> lane) & 1) && slot < n_hist) out[slot] = g + lane;
-        off += __popcll(ballot);
-    });
+    }
     CUSA_TRACE_POINT(4);
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;

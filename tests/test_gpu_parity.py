@@ -163,6 +163,31 @@ def test_ties_quantised_keys():
     _with_keys(w, quant)
 
 
+@pytest.mark.parametrize("L", [12000, 40000])
+def test_ties_on_long_rows_overflow_the_candidate_list(L):
+    """Rows long enough for the top-k kernel's LDS candidate list (keys in registers, and streamed
+    from memory), with so many equal scores that the list cannot hold the candidates."""
+    w = small(f"longties{L}", batch=1, seq_len=L, budget=512, window=128)
+
+    def quant(k):
+        k.copy_(torch.sign(k) * (k.abs() > 1.5))   # most keys are zero: most scores are exactly 0
+    _with_keys(w, quant)
+
+    def alleq(k):
+        k[:] = k[:, :, :1].clone()
+    inp, r = _with_keys(small(f"longeq{L}", batch=1, seq_len=L, budget=512, window=128), alleq)
+    torch.cuda.synchronize()
+    rho = r.rho_head()[0].cpu().numpy()
+    assert (rho == np.arange(rho.shape[0])[:, None]).all()
+
+
+@pytest.mark.parametrize("L", [12000, 40000])
+def test_long_rows_with_distinct_scores_use_the_candidate_list(L):
+    w = small(f"long{L}", batch=2, seq_len=L, min_seq_len=L - 3000, budget=1024, window=256, n_planted=8)
+    inp, r, sched = run_and_check(w)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+
+
 def test_selection_is_deterministic_across_runs():
     w = small("det", batch=2, seq_len=4000, budget=512, window=128)
     inp = wl.make_inputs(w, DEV)
