@@ -310,9 +310,9 @@ template <int GQ>
 void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
                   int H, int budget, int window, int tiles_per_seq, int n_tiles) {
     if (paged)
-        launch(KID_SCORE, score_kernel<GQ, true>, grid, 256, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
     else
-        launch(KID_SCORE, score_kernel<GQ, false>, grid, 256, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
 }
 
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
@@ -331,7 +331,8 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
         if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
         const int n_tiles = (int)n_tiles64;
-        const int grid = n_tiles < SCORE_GRID ? n_tiles : SCORE_GRID;   // two 64 KB tiles fit a CU's LDS
+        const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
+        const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
         {
             switch (g) {
                 case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;

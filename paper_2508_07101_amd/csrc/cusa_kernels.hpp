@@ -76,10 +76,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 
 // ---------------------------------------------------------------- scoring pass
 //
-// A tile is 256 consecutive candidate keys of one KV head (64 KB), scored against the GQ
-// query heads of its group.  The tile is fetched with coalesced 16-byte loads (16 lanes per
-// 256-byte row) and parked in LDS, chunk c of row r at slot c ^ (r & 7) so that row reads by
-// consecutive lanes fall into distinct 16-byte bank groups.  Then every lane owns one row.
+// The unit of work is a tile of 64 consecutive candidate keys of one KV head (16 KB), scored
+// against the GQ query heads of its group by ONE wave; the four waves of a workgroup work
+// independently (own LDS region, own copy of q, no workgroup barrier anywhere), so that while
+// one wave scores, the others' loads keep the memory system busy.  A tile is fetched with
+// coalesced 16-byte loads (16 lanes per 256-byte row, 4 rows per instruction) and parked in
+// LDS, chunk c of row r at slot c ^ (r & 7) so that row reads by consecutive lanes fall into
+// distinct 16-byte bank groups.  Then every lane owns one row.
 //
 // The dot products run on the matrix cores with V_MFMA_F32_4X4X1_16B_F32: one instruction
 // takes, per lane, one binary32 element of q (head = lane % 4) and one of K (the lane's row)
@@ -88,31 +91,40 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // addition per instruction, so walking the 128 columns in order is the left-to-right
 // binary32 sum the selection's bit-exactness rests on -- no reordering inside the
 // instruction can occur.  (Checked bit for bit against a scalar fmaf chain on the device.)
-// q sits in LDS as binary32, head stride padded to 132 floats (distinct banks per head).
+// q sits in LDS as bf16, head stride padded to 136 elements (distinct banks per head).
 //
-// A workgroup walks tiles id = blockIdx.x, +gridDim.x, ... (id = (sequence, KV head, tile)
-// in that order) and issues the loads of its next tile before it scores the current one,
-// so a CU always has loads in flight.  Rows past the candidate range are clamped to the
-// last candidate (loads stay unconditional and batched); their scores are not stored.
+// Wave number v of the grid walks tiles id = v, v + waves, ... (id = (sequence, KV head, tile)
+// in that order) and issues the loads of its next tile before it scores the current one.
+// Rows past the candidate range are clamped to the last candidate (loads stay unconditional
+// and batched); their scores are not stored.
 
-constexpr int SCORE_ROWS = 256;
+constexpr int SCORE_ROWS = 64;
+constexpr int SCORE_WAVES = 4;
+
+// Forward declaration: wave-local LDS ordering (defined with the attention kernel).
+__device__ __forceinline__ void wave_lds_sync();
 
 template <int GQ, bool PAGED>
-__global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint16_t* __restrict__ q,
-                                                     float* __restrict__ P, int64_t ldp, int H,
-                                                     int budget, int window, int tiles_per_seq, int n_tiles) {
+__global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(KvView kv, const uint16_t* __restrict__ q,
+                                                                  float* __restrict__ P, int64_t ldp, int H,
+                                                                  int budget, int window, int tiles_per_seq,
+                                                                  int n_tiles) {
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
-    constexpr int QS = 132;                           // padded head stride of q in LDS
-    constexpr int QN = (GQ * D + 255) / 256;          // q elements staged per thread
-    __shared__ u32x4 tile[SCORE_ROWS * 16];
-    __shared__ float qs[SETS * 4 * QS];
-    const int tid = threadIdx.x, lane = tid & 63;
+    constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
+    constexpr int QL = (GQ * D * 2 + 1023) / 1024;    // 16-byte q loads per lane
+    __shared__ u32x4 tile_all[SCORE_WAVES][SCORE_ROWS * 16];
+    __shared__ __attribute__((aligned(16))) uint16_t q_all[SCORE_WAVES][SETS * 4 * QSB];
+    const int lane = threadIdx.x & 63, r = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u32x4* const tile = tile_all[wave];
+    uint16_t* const qs = q_all[wave];
     const int G = kv.G;
-    for (int i = tid; i < SETS * 4 * QS; i += 256) qs[i] = 0.0f;   // heads beyond GQ contribute zeros
+    const int stride = gridDim.x * SCORE_WAVES;
+    for (int i = lane; i < SETS * 4 * QSB / 2; i += 64) reinterpret_cast<uint32_t*>(qs)[i] = 0u;   // heads beyond GQ contribute zeros
 
-    // next tile at or after `id` (stride gridDim.x) that has candidates; n_tiles if none
+    // next tile at or after `id` (stride: all waves of the grid) that has candidates; n_tiles if none
     auto next_valid = [&](int id, int& b, int& kvh, int& t0, int& Lc) __attribute__((always_inline)) {
-        for (; id < n_tiles; id += gridDim.x) {
+        for (; id < n_tiles; id += stride) {
             const int seq_head = id / tiles_per_seq;
             b = seq_head / G;
             kvh = seq_head - b * G;
@@ -124,26 +136,30 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint16_t* _
         return n_tiles;
     };
     int b = 0, kvh = 0, t0 = 0, Lc = 0;               // tile being scored (none yet)
+    int qb = -1, qkvh = -1;                           // the group whose q is in LDS
     bool have_cur = false;
     int nb, nkvh, nt0, nLc;
-    int nid = next_valid(blockIdx.x, nb, nkvh, nt0, nLc);
+    int nid = next_valid(blockIdx.x * SCORE_WAVES + wave, nb, nkvh, nt0, nLc);
     while (true) {
         const bool have_next = nid < n_tiles;
+        const bool new_q = have_next && (nb != qb || nkvh != qkvh);
         u32x4 stage[16];
-        uint16_t qstage[QN];
+        u32x4 qstage[QL];
         if (have_next) {                              // loads of the next tile, in flight during the scoring below
             int64_t off[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int chunk = i * 256 + tid;
-                const int t = min(nt0 + (chunk >> 4), nLc - 1);
-                off[i] = row_offset<PAGED>(kv, nb, nkvh, t) + (chunk & 15) * 8;
+                const int t = min(nt0 + i * 4 + r, nLc - 1);
+                off[i] = row_offset<PAGED>(kv, nb, nkvh, t) + c * 8;
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) stage[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
-            const uint16_t* __restrict__ qg = q + ((int64_t)nb * H + (int64_t)nkvh * GQ) * D;
+            if (new_q) {
+                const uint16_t* __restrict__ qg = q + ((int64_t)nb * H + (int64_t)nkvh * GQ) * D;
 #pragma unroll
-            for (int j = 0; j < QN; ++j) qstage[j] = qg[min(j * 256 + tid, GQ * D - 1)];
+                for (int j = 0; j < QL; ++j)
+                    qstage[j] = *reinterpret_cast<const u32x4*>(qg + min((j * 64 + lane) * 8, GQ * D - 8));
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         if (have_cur) {
@@ -151,49 +167,51 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint16_t* _
 #pragma unroll
             for (int s = 0; s < SETS; ++s) acc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int c = 0; c < 16; ++c) {
-                const u32x4 w = tile[tid * 16 + (c ^ (tid & 7))];
+            for (int cc = 0; cc < 16; ++cc) {
+                const u32x4 w = tile[lane * 16 + (cc ^ (lane & 7))];
                 float kf[8];
                 unpack8(make_uint4(w.x, w.y, w.z, w.w), kf);
+                float qf[SETS][8];
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    f32x4 qa[SETS];
+                for (int s = 0; s < SETS; ++s) {
+                    const u32x4 qw = *reinterpret_cast<const u32x4*>(&qs[(s * 4 + (lane & 3)) * QSB + cc * 8]);
+                    unpack8(make_uint4(qw.x, qw.y, qw.z, qw.w), qf[s]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
 #pragma unroll
                     for (int s = 0; s < SETS; ++s)
-                        qa[s] = *reinterpret_cast<const f32x4*>(&qs[(s * 4 + (lane & 3)) * QS + c * 8 + half * 4]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-#pragma unroll
-                        for (int s = 0; s < SETS; ++s)
-                            acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qa[s][e], kf[half * 4 + e], acc[s], 0, 0, 0);
-                }
+                        acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], acc[s], 0, 0, 0);
             }
-            const int t = t0 + tid;
+            const int t = t0 + lane;
             if (t < Lc) {
 #pragma unroll
                 for (int s = 0; s < SETS; ++s)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (s * 4 + r < GQ) P[((int64_t)b * H + kvh * GQ + s * 4 + r) * ldp + t] = acc[s][r];
+                    for (int h = 0; h < 4; ++h)
+                        if (s * 4 + h < GQ) P[((int64_t)b * H + kvh * GQ + s * 4 + h) * ldp + t] = acc[s][h];
             }
         }
         if (!have_next) break;
-        __syncthreads();                              // everyone is done reading the tile in LDS
+        wave_lds_sync();                              // this wave is done reading its tile and q
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int chunk = i * 256 + tid;
-            const int row = chunk >> 4, c = chunk & 15;
+            const int row = i * 4 + r;
             tile[row * 16 + (c ^ (row & 7))] = stage[i];
         }
+        if (new_q) {
 #pragma unroll
-        for (int j = 0; j < QN; ++j) {
-            const int i = j * 256 + tid;
-            if (i < GQ * D) qs[(i >> 7) * QS + (i & (D - 1))] = __uint_as_float((uint32_t)qstage[j] << 16);
+            for (int j = 0; j < QL; ++j) {
+                const int e0 = (j * 64 + lane) * 8;   // first of the lane's 8 consecutive elements of the group's q
+                if (e0 < GQ * D) *reinterpret_cast<u32x4*>(&qs[(e0 >> 7) * QSB + (e0 & (D - 1))]) = qstage[j];
+            }
+            qb = nb;
+            qkvh = nkvh;
         }
-        __syncthreads();
+        wave_lds_sync();
         b = nb; kvh = nkvh; t0 = nt0; Lc = nLc;
         have_cur = true;
-        nid = next_valid(nid + gridDim.x, nb, nkvh, nt0, nLc);
+        nid = next_valid(nid + stride, nb, nkvh, nt0, nLc);
     }
 }
 
