@@ -142,7 +142,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 constexpr int SCORE_GRID = 512;    // persistent scoring workgroups: 2 per CU on 256 CUs
 constexpr int MAX_SPLITS = 256;
 constexpr int TARGET_WGS = 512;     // two resident workgroups per CU
-constexpr int CHUNK_CAP = 4096;
+constexpr int CHUNK_CAP = 2048;
 
 struct AttnPlan {
     int ti;        // row-load instructions per wave iteration (4 or 8)

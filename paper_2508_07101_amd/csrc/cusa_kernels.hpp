@@ -949,7 +949,11 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[ATTN_WAVES][SETS * 4 * QSB];   // a private copy of q per wave
 
     CUSA_TRACE_POINT(0);
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
+    // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
+    // block spreads them evenly over the XCDs instead of loading the first ones.
+    const int kvh = blockIdx.y, b = blockIdx.z;
+    const int split = (int)((blockIdx.x + kvh + gridDim.y * b) % (unsigned)n_splits);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
     const int begin = split * chunk;
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
