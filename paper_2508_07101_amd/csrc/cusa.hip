@@ -222,9 +222,9 @@ void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& vie
                          uint16_t* out, int n_splits, int chunk, int H) {
     const int kid = SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL;
     if (paged)
-        launch(kid, attn_kernel<GQ, TI, SPARSE, true>, grid, ATTN_THREADS, 0, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, true>, grid, ATTN_THREADS, 0, s, idx, cnt, view.seq_lens, q, budget, n_splits, chunk, view.G, scale, pa, pm, out, view);
     else
-        launch(kid, attn_kernel<GQ, TI, SPARSE, false>, grid, ATTN_THREADS, 0, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, false>, grid, ATTN_THREADS, 0, s, idx, cnt, view.seq_lens, q, budget, n_splits, chunk, view.G, scale, pa, pm, out, view);
 }
 
 template <int GQ, bool SPARSE>

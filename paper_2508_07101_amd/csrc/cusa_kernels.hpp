@@ -931,9 +931,9 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 template <int GQ, int TI, bool SPARSE, bool PAGED>
 __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
-    KvView kv, const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, int budget, float scale_log2e, float* __restrict__ part_acc,
-    float* __restrict__ part_ml, uint16_t* __restrict__ out, int n_splits, int chunk, int H) {
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
+    const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
+    float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, KvView kv) {
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
@@ -952,8 +952,8 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
-    const int kvh = blockIdx.y, b = blockIdx.z;
-    const int split = (int)((blockIdx.x + kvh + gridDim.y * b) % (unsigned)n_splits);
+    const int kvh = blockIdx.y, b = blockIdx.z, H = G * GQ;
+    const int split = (int)((blockIdx.x + kvh + G * b) % (unsigned)n_splits);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
     const int begin = split * chunk;
     const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
@@ -979,7 +979,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         if (h >= GQ) qv[s] = u32x4{0u, 0u, 0u, 0u};
     }
     bool q_parked = false;
-    const int L = kv.seq_lens[b];
+    const int L = seq_lens[b];
     const int n = SPARSE ? min(cnt[b], budget) : L;
     // Everything the first tile's addresses depend on is requested above and has to be here
     // before the first branch; otherwise the compiler sinks each load behind the branch that
