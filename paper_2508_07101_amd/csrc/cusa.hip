@@ -310,9 +310,9 @@ template <int GQ>
 void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
                   int H, int budget, int window, int tiles_per_seq, int n_tiles) {
     if (paged)
-        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles, view);
     else
-        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, view, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles);
+        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles, view);
 }
 
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,

@@ -105,10 +105,10 @@ constexpr int SCORE_WAVES = 4;
 __device__ __forceinline__ void wave_lds_sync();
 
 template <int GQ, bool PAGED>
-__global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(KvView kv, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t* __restrict__ q,
                                                                   float* __restrict__ P, int64_t ldp, int H,
                                                                   int budget, int window, int tiles_per_seq,
-                                                                  int n_tiles) {
+                                                                  int n_tiles, KvView kv) {
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
     constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
     constexpr int QL = (GQ * D * 2 + 1023) / 1024;    // 16-byte q loads per lane
