@@ -134,7 +134,9 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
                              void* ws, size_t ws_bytes, void* stream);
 
 /* FullAttention(q, C[:]) of Alg. 1 (Eq. 1 over all L_b tokens); also the
- * baseline the sparse path is compared with.  budget/window/topk are ignored. */
+ * baseline the sparse path is compared with.  budget, window and topk_per_head
+ * do not enter the result, but params is validated as a whole (so they must
+ * still be consistent) and sizes the workspace.  out as in cusa_sparse_attn. */
 cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv,
                            void* out, void* ws, size_t ws_bytes, void* stream);
 
@@ -156,11 +158,13 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
 const char* cusa_strerror(cusa_status status);
 
 /* ---- per-kernel timing (benchmark support; not part of the method) ---------
- * While enabled, every kernel the library enqueues is bracketed by HIP events
- * on the launch stream.  cusa_profile_read waits for those events and returns,
- * for kernel id i < n, the number of launches and the summed milliseconds since
- * the last reset.  Enabling costs host time per launch and creates events, so it
- * must not be on under graph capture.  Returns the number of kernel ids. */
+ * While enabled, every kernel the library enqueues is launched with a start and a
+ * stop event that the runtime fills from the dispatch's own begin and end time
+ * stamps (hipExtLaunchKernelGGL), i.e. the duration a kernel trace reports.
+ * cusa_profile_read waits for those events and returns, for kernel id i < n, the
+ * number of launches and the summed milliseconds since the last reset.  Enabling
+ * costs host time per launch and creates events, so it must not be on under graph
+ * capture.  cusa_profile_num_kernels returns the number of kernel ids. */
 int32_t     cusa_profile_num_kernels(void);
 const char* cusa_profile_kernel_name(int32_t id);
 void        cusa_profile_enable(int32_t on);

@@ -207,6 +207,11 @@ cusa_status check_ws(const WsLayout& w, void* ws, size_t ws_bytes) {
     return CUSA_OK;
 }
 
+// The union kernel's bitmap over candidate positions has to fit LDS.
+cusa_status check_select_length(const cusa_params* p, const cusa_kv* kv) {
+    return (int64_t)kv->max_seq_len - p->window > UNION_MAX_POSITIONS ? CUSA_ERR_UNSUPPORTED : CUSA_OK;
+}
+
 template <typename T>
 T* ws_ptr(void* ws, size_t off) {
     return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
@@ -324,7 +329,6 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
     float* P = ws_ptr<float>(ws, w.scores);
     int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
 
-    if ((int64_t)kv->max_seq_len - p->window > UNION_MAX_POSITIONS) return CUSA_ERR_UNSUPPORTED;
     if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
         const int lc_max = kv->max_seq_len - p->window;
         const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
@@ -398,6 +402,7 @@ cusa_status cusa_select(const cusa_params* params, const void* q, const cusa_kv*
     if (st != CUSA_OK) return st;
     if ((st = check_kv(params, kv)) != CUSA_OK) return st;
     if (!q || !idx || !cnt || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    if ((st = check_select_length(params, kv)) != CUSA_OK) return st;
     const WsLayout w = make_layout(params, kv->max_seq_len);
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     return run_select(params, q, kv, idx, cnt, ws, w, static_cast<hipStream_t>(stream));
@@ -442,7 +447,10 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
         if (kv_layers[i].max_seq_len > max_len) max_len = kv_layers[i].max_seq_len;
         switch (layer_kind[i]) {
             case CUSA_LAYER_FULL: break;
-            case CUSA_LAYER_SELECT: have_rho = true; break;
+            case CUSA_LAYER_SELECT:
+                if ((st = check_select_length(params, &kv_layers[i])) != CUSA_OK) return st;
+                have_rho = true;
+                break;
             case CUSA_LAYER_SPARSE:
                 if (!have_rho) return CUSA_ERR_INVALID_ARG;
                 break;

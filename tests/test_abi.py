@@ -83,6 +83,9 @@ def test_null_and_misshapen_arguments_are_rejected_before_any_launch():
     assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(pg), fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
     pg = cb.CusaKv(0x1000, 0x2000, cb.KV_PAGED, 0, 0, 0, 0x4000, 10, 16, 100, 0x3000, 4096)
     assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(pg), fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    # selection on sequences longer than the union kernel's on-chip bitmap covers
+    lng = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 2_000_000 * 128, 128, None, 0, 0, 0, 0x3000, 2_000_000)
+    assert lib.cusa_select(ctypes.byref(p), fake, ctypes.byref(lng), fake, fake, fake, 1 << 40, None) == cb.ERR_UNSUPPORTED
     # unknown layout, missing seq_lens
     bad = cb.CusaKv(0x1000, 0x2000, 5, 0, 4096 * 128, 128, None, 0, 0, 0, 0x3000, 4096)
     assert lib.cusa_sparse_attn(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
