@@ -188,6 +188,43 @@ def test_long_rows_with_distinct_scores_use_the_candidate_list(L):
     check_attention(inp, r, 1, LAYER_SPARSE)
 
 
+def test_large_topk_per_head_uses_the_widest_sort():
+    """k between 4097 and 8192: eight sorted composites per thread and the largest LDS footprint."""
+    w = small("bigk", batch=1, seq_len=20000, budget=6144, window=1024, n_planted=8)
+    inp, r, sched = run_and_check(w)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+
+
+def test_group_of_eight_on_long_paged_rows():
+    w = small("g8long", n_q_heads=64, n_kv_heads=8, batch=2, seq_len=36000, min_seq_len=30000, paged=True,
+              budget=1024, window=256)
+    inp, r, sched = run_and_check(w)
+    for i, kind in enumerate(sched):
+        check_attention(inp, r, i, kind, seqs=[1])
+
+
+def test_repeated_steps_are_bit_identical():
+    """Races between waves or workgroups would show up as run-to-run differences."""
+    w = small("repeat", n_layers=3, schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE), batch=5, seq_len=6000,
+              lengths=(6000, 700, 2049, 4097, 300), paged=True, budget=512, window=128, lowrank=4)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    ref = None
+    for _ in range(12):
+        r.idx.fill_(-1)
+        for o in r.outs:
+            o.zero_()
+        r.run()
+        torch.cuda.synchronize()
+        cur = [r.idx.clone(), r.cnt.clone()] + [o.clone() for o in r.outs]
+        cnt = cur[1].cpu().numpy()
+        for b in range(w.batch):
+            cur[0][b, cnt[b]:] = -1                      # entries past cnt are unspecified
+        if ref is not None:
+            assert all(torch.equal(a, b_) for a, b_ in zip(cur, ref))
+        ref = cur
+
+
 def test_selection_is_deterministic_across_runs():
     w = small("det", batch=2, seq_len=4000, budget=512, window=128)
     inp = wl.make_inputs(w, DEV)
