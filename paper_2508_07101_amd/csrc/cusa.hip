@@ -306,6 +306,7 @@ cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp,
 template <int ITEMS>
 cusa_status launch_topk(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
                         int32_t* rho_head, int H, int k, int budget, int window) {
+    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
     if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
     if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
     return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
