@@ -735,9 +735,14 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         int wave_added = 0;
 #pragma unroll
         for (int u = 0; u < UNION_UNROLL; ++u) {
+            // Neighbouring slots are neighbouring heads at one rank and often name the same token;
+            // a lane whose left neighbour in its 16-lane row has the same pick leaves the atomic to it
+            // (same-address LDS atomics of one instruction are carried out one after the other).
+            const int left = __builtin_amdgcn_update_dpp(-2, tok[u], 0x111, 0xF, 0xF, false);   // row_shr:1; -2 into lane 0 of a row
+            const bool lead = tok[u] >= 0 && tok[u] != left;
             const uint32_t bit = 1u << (tok[u] & 31);
-            const uint32_t old = atomicOr(&bits[tok[u] >= 0 ? tok[u] >> 5 : 0], tok[u] >= 0 ? bit : 0u);
-            const bool wn = tok[u] >= 0 && !(old & bit);
+            const uint32_t old = atomicOr(&bits[lead ? tok[u] >> 5 : 0], lead ? bit : 0u);
+            const bool wn = lead && !(old & bit);
             if (wn) won |= 1u << u;
             wave_added += __popcll(__ballot(wn));
         }
