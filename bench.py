@@ -2,8 +2,8 @@
 """Benchmark of the CUSA decode hot path on one MI355X.
 
 A "step" is the attention part of one decode step of the paper's Alg. 1 over all layers of
-the workload: full-attention layers, the selection layer (full attention + scoring + per-head
-top-k + cross-head union + window) and the sparse-attention layers that reuse rho.  Inputs are
+the workload: full-attention layers, the selection layer (full attention that also emits the
+scores + per-head top-k + cross-head union + window) and the sparse-attention layers that reuse rho.  Inputs are
 seeded, synthetic and resident in HBM before the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
@@ -60,6 +60,8 @@ def kernel_bytes(w, lens, acc):
         "attn_kernel<full>": sum(acc.full_attn_bytes(G, L) for L in lens),
         "attn_kernel<sparse>": sum(acc.sparse_attn_bytes(G, K, L) for L in lens),
         "score_kernel": sum(acc.score_bytes(G, L, K, W) for L in lens),
+        # the selection layer's pass: K and V once, the scores come from the same K rows
+        "attn_kernel<full+score>": sum(acc.full_attn_bytes(G, L) for L in lens),
     }
 
 

@@ -143,8 +143,10 @@ cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_
 /* Attention part of one decode step of Alg. 1 over n_layers layers.
  * layer_kind  host int32[n_layers] of cusa_layer_kind.  FULL: full attention.
  *             SELECT: full attention for this layer's output, then rho is rebuilt
- *             from this layer's q and K.  SPARSE: sparse attention over the
- *             current rho.  A SPARSE layer with no SELECT layer before it in this
+ *             from this layer's q and K (the scores P are written by the same pass
+ *             over K that computes the output, bit for bit those of cusa_select;
+ *             the output agrees with cusa_full_attn up to binary32 rounding order).
+ *             SPARSE: sparse attention over the current rho.  A SPARSE layer with no SELECT layer before it in this
  *             call is INVALID_ARG (Alg. 1 starts with rho empty).
  * q_layers    host array of n_layers device pointers, each bf16 [batch][H][128].
  * kv_layers   host array of n_layers cache views.

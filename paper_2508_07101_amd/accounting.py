@@ -39,15 +39,19 @@ def score_bytes(G: int, L: int, budget: int, window: int, d: int = 128) -> int:
 
 
 def step_bytes(schedule: Sequence[int], seq_lens: Iterable[int], G: int, budget: int,
-               window: int, d: int = 128) -> dict:
-    """Per-kind and total algorithmic bytes of one decode step over all sequences."""
+               window: int, d: int = 128, fused_select: bool = True) -> dict:
+    """Per-kind and total algorithmic bytes of one decode step over all sequences.
+
+    fused_select: the selection layer scores its tokens in the same pass that computes its output
+    (as the decode step does), so its K rows count once; False counts the separate scoring pass of
+    a stand-alone selection call as well."""
     out = {"full": 0, "score": 0, "sparse": 0}
     lens = list(seq_lens)
     for kind in schedule:
         for L in lens:
             if kind in (LAYER_FULL, LAYER_SELECT):
                 out["full"] += full_attn_bytes(G, L, d)
-            if kind == LAYER_SELECT:
+            if kind == LAYER_SELECT and not fused_select:
                 out["score"] += score_bytes(G, L, budget, window, d)
             if kind == LAYER_SPARSE:
                 out["sparse"] += sparse_attn_bytes(G, budget, L, d)

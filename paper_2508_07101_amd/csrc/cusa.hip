@@ -18,9 +18,10 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
-                                             "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel"};
+                                             "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
+                                             "attn_kernel<full+score>"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -155,12 +156,12 @@ struct AttnPlan {
 // that a large ragged batch is cut into equal pieces instead of one piece per sequence.
 // Workgroups with long runs (1024 tokens or more) load 8 rows per lane and iteration, which keeps
 // more bytes in flight; short runs are faster with 4 (measured on all five workloads).
-AttnPlan plan_attn(int n_max, int BG, int g) {
+AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
     (void)g;
     AttnPlan pl;
     int64_t chunk = ((int64_t)n_max * BG + TARGET_WGS - 1) / TARGET_WGS;
     if (chunk > CHUNK_CAP) chunk = CHUNK_CAP;
-    pl.ti = chunk >= 1024 ? 8 : 4;
+    pl.ti = wide ? (chunk >= 512 ? 16 : 8) : chunk >= 1024 ? 8 : 4;
     const int wg_tile = pl.ti * 4 * ATTN_WAVES;
     chunk = (chunk + wg_tile - 1) / wg_tile * wg_tile;
     if ((n_max + chunk - 1) / chunk > MAX_SPLITS) {
@@ -221,54 +222,91 @@ cusa_status launch_status() { return hipGetLastError() == hipSuccess ? CUSA_OK :
 
 // ------------------------------------------------------------------ launches
 
-template <int GQ, int TI, bool SPARSE>
-void launch_attn_partial(bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
-                         const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                         uint16_t* out, int n_splits, int chunk, int H) {
-    const int kid = SPARSE ? KID_ATTN_SPARSE : KID_ATTN_FULL;
-    if (paged)
-        launch(kid, attn_kernel<GQ, TI, SPARSE, true>, grid, ATTN_THREADS, 0, s, idx, cnt, view.seq_lens, q, budget, n_splits, chunk, view.G, scale, pa, pm, out, view);
+// What a pass over all tokens of a selection layer also emits (scores of the candidate range).
+struct ScoreOut {
+    float* P = nullptr;     // nullptr: plain attention
+    int64_t ldp = 0;
+    int window = 0;
+};
+
+struct AttnArgs {
+    bool paged;
+    dim3 grid;
+    hipStream_t s;
+    KvView view;
+    const uint16_t* q;
+    const int32_t* idx;
+    const int32_t* cnt;
+    int budget;
+    float scale;
+    float* pa;
+    float* pm;
+    uint16_t* out;
+    int n_splits, chunk;
+    ScoreOut score;
+};
+
+template <int GQ, int TI, bool SPARSE, bool SCORE>
+void launch_attn_partial(const AttnArgs& a) {
+    const int kid = SPARSE ? KID_ATTN_SPARSE : SCORE ? KID_ATTN_SELECT : KID_ATTN_FULL;
+    if (a.paged)
+        launch(kid, attn_kernel<GQ, TI, SPARSE, true, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, a.view);
     else
-        launch(kid, attn_kernel<GQ, TI, SPARSE, false>, grid, ATTN_THREADS, 0, s, idx, cnt, view.seq_lens, q, budget, n_splits, chunk, view.G, scale, pa, pm, out, view);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, false, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, a.view);
 }
 
 template <int GQ, bool SPARSE>
-void launch_attn_ti(int ti, bool paged, dim3 grid, hipStream_t s, const KvView& view, const uint16_t* q,
-                    const int32_t* idx, const int32_t* cnt, int budget, float scale, float* pa, float* pm,
-                    uint16_t* out, int n_splits, int chunk, int H) {
+void launch_attn_ti(int ti, const AttnArgs& a) {
+    if constexpr (!SPARSE) {
+        if (a.score.P) {                              // the scoring chain repeats work for tiles under 64 tokens: always the wider tile
+            if (ti == 16) launch_attn_partial<GQ, 16, false, true>(a);
+            else launch_attn_partial<GQ, 8, false, true>(a);
+            return;
+        }
+    }
     if (ti == 8) {
-        launch_attn_partial<GQ, 8, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+        launch_attn_partial<GQ, 8, SPARSE, false>(a);
         return;
     }
-    launch_attn_partial<GQ, 4, SPARSE>(paged, grid, s, view, q, idx, cnt, budget, scale, pa, pm, out, n_splits, chunk, H);
+    launch_attn_partial<GQ, 4, SPARSE, false>(a);
 }
 
 // Attention over all tokens (idx == nullptr) or over idx/cnt; n_max bounds the token count.
+// With score.P set (all tokens only) the pass also writes the selection scores.
 template <bool SPARSE>
 cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv, const int32_t* idx,
-                          const int32_t* cnt, int n_max, void* out, void* ws, const WsLayout& w, hipStream_t s) {
+                          const int32_t* cnt, int n_max, void* out, void* ws, const WsLayout& w, hipStream_t s,
+                          ScoreOut score = ScoreOut()) {
     const int g = p->n_q_heads / p->n_kv_heads, BG = p->batch * p->n_kv_heads, H = p->n_q_heads;
-    const AttnPlan pl = plan_attn(n_max, BG, g);
+    const AttnPlan pl = plan_attn(n_max, BG, g, score.P != nullptr);
     if (pl.n_splits > w.max_splits) return CUSA_ERR_WORKSPACE_TOO_SMALL;
-    const KvView view = make_view(p, kv);
-    const bool paged = kv->layout == CUSA_KV_PAGED;
-    const float scale = p->sm_scale * 1.4426950408889634f;
-    float* pa = ws_ptr<float>(ws, w.part_acc);
-    float* pm = ws_ptr<float>(ws, w.part_ml);
-    const uint16_t* qq = static_cast<const uint16_t*>(q);
-    uint16_t* oo = static_cast<uint16_t*>(out);
-    dim3 grid(pl.n_splits, p->n_kv_heads, p->batch);
-    {
-        switch (g) {
-            case 1: launch_attn_ti<1, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
-            case 2: launch_attn_ti<2, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
-            case 4: launch_attn_ti<4, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
-            default: launch_attn_ti<8, SPARSE>(pl.ti, paged, grid, s, view, qq, idx, cnt, p->budget, scale, pa, pm, oo, pl.n_splits, pl.chunk, H); break;
-        }
+    AttnArgs a;
+    a.paged = kv->layout == CUSA_KV_PAGED;
+    a.grid = dim3(pl.n_splits, p->n_kv_heads, p->batch);
+    a.s = s;
+    a.view = make_view(p, kv);
+    a.q = static_cast<const uint16_t*>(q);
+    a.idx = idx;
+    a.cnt = cnt;
+    a.budget = p->budget;
+    a.scale = p->sm_scale * 1.4426950408889634f;
+    a.pa = ws_ptr<float>(ws, w.part_acc);
+    a.pm = ws_ptr<float>(ws, w.part_ml);
+    a.out = static_cast<uint16_t*>(out);
+    a.n_splits = pl.n_splits;
+    a.chunk = pl.chunk;
+    a.score = score;
+    switch (g) {
+        case 1: launch_attn_ti<1, SPARSE>(pl.ti, a); break;
+        case 2: launch_attn_ti<2, SPARSE>(pl.ti, a); break;
+        case 4: launch_attn_ti<4, SPARSE>(pl.ti, a); break;
+        default: launch_attn_ti<8, SPARSE>(pl.ti, a); break;
     }
     if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
     if (pl.n_splits > 1) {
-        launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, pa, pm, oo, SPARSE ? cnt : kv->seq_lens,
+        launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, a.pa, a.pm, a.out, SPARSE ? cnt : kv->seq_lens,
                SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H);
     }
     return launch_status();
@@ -321,8 +359,9 @@ void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const
         launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles, view);
 }
 
+// scores_ready: P was already written by the layer's attention pass (cusa_decode_step).
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
-                       const WsLayout& w, hipStream_t s) {
+                       const WsLayout& w, hipStream_t s, bool scores_ready = false) {
     const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
     const KvView view = make_view(p, kv);
     const bool paged = kv->layout == CUSA_KV_PAGED;
@@ -332,21 +371,23 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
 
     if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
         const int lc_max = kv->max_seq_len - p->window;
-        const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
-        const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
-        if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
-        const int n_tiles = (int)n_tiles64;
-        const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
-        const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
-        {
-            switch (g) {
-                case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+        if (!scores_ready) {
+            const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
+            const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
+            if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
+            const int n_tiles = (int)n_tiles64;
+            const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
+            const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
+            {
+                switch (g) {
+                    case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                    case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                    case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                    default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
+                }
             }
+            if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         }
-        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
         cusa_status st;
         {
@@ -467,10 +508,17 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
             const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
             st = run_attention<true>(params, q_layers[i], kv, idx, cnt, n_max, out_layers[i], ws, w, s);
         } else {
+            // a selection layer's pass over all tokens also writes the scores: K is read once
+            ScoreOut score;
+            if (layer_kind[i] == CUSA_LAYER_SELECT && kv->max_seq_len > params->budget) {
+                score.P = ws_ptr<float>(ws, w.scores);
+                score.ldp = w.ldp;
+                score.window = params->window;
+            }
             st = run_attention<false>(params, q_layers[i], kv, nullptr, nullptr, kv->max_seq_len, out_layers[i], ws,
-                                      w, s);
+                                      w, s, score);
             if (st == CUSA_OK && layer_kind[i] == CUSA_LAYER_SELECT)
-                st = run_select(params, q_layers[i], kv, idx, cnt, ws, w, s);
+                st = run_select(params, q_layers[i], kv, idx, cnt, ws, w, s, score.P != nullptr);
         }
         if (st != CUSA_OK) return st;
     }

@@ -935,11 +935,18 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int GQ, int TI, bool SPARSE, bool PAGED>
-__global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
+// SCORE (selection layer, all tokens): the scores of the candidate range [0, L - window) are also
+// written to P[b][head][t] (row stride ldp), bit for bit what score_kernel writes, so the layer's K
+// is read once for both (Alg. 1 computes the layer's output and P from the same K).  q.k then runs
+// as the k = 1 MFMA chain of score_kernel -- the pinned left-to-right binary32 sum -- instead of
+// the k = 4 bf16 MFMA, and the softmax uses those same values.
+template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false>
+__global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
     const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
-    float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, KvView kv) {
+    float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ P,
+    int64_t ldp, int window, KvView kv) {
+    static_assert(!(SCORE && SPARSE), "scores are emitted by the pass over all tokens");
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
@@ -951,7 +958,9 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
     u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
-    __shared__ f32x4 pbuf[ATTN_WAVES][TILE][SETS];    // a wave's softmax numerators, by token
+    // A wave's softmax numerators, by token, take the place of its K rows once those are scored.
+    static_assert(TILE * 256 >= TILE * SETS * 16, "the numerators must fit the K tile buffer");
+    f32x4(*const pbuf)[SETS] = reinterpret_cast<f32x4(*)[SETS]>(ktile);
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[ATTN_WAVES][SETS * 4 * QSB];   // a private copy of q per wave
 
     CUSA_TRACE_POINT(0);
@@ -1049,17 +1058,43 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
         f32x4 sc[SETS];
 #pragma unroll
         for (int s = 0; s < SETS; ++s) sc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (SCORE) {
 #pragma unroll
-        for (int cc = 0; cc < 16; ++cc) {
-            const u32x4 kw = ktile[tl * 16 + (cc ^ (tl & 7))];
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const uint2 kb = half == 0 ? make_uint2(kw.x, kw.y) : make_uint2(kw.z, kw.w);
-                const s16x4 bq = __builtin_bit_cast(s16x4, kb);
+            for (int cc = 0; cc < 16; ++cc) {
+                const u32x4 kw = ktile[tl * 16 + (cc ^ (tl & 7))];
+                float kf[8];
+                unpack8(make_uint4(kw.x, kw.y, kw.z, kw.w), kf);
+                float qf[SETS][8];
 #pragma unroll
                 for (int s = 0; s < SETS; ++s) {
-                    const s16x4 aq = *reinterpret_cast<const s16x4*>(&qlds[(s * 4 + (lane & 3)) * QSB + cc * 8 + half * 4]);
-                    sc[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aq, bq, sc[s], 0, 0, 0);
+                    const u32x4 qw = *reinterpret_cast<const u32x4*>(&qlds[(s * 4 + (lane & 3)) * QSB + cc * 8]);
+                    unpack8(make_uint4(qw.x, qw.y, qw.z, qw.w), qf[s]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int s = 0; s < SETS; ++s)
+                        sc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], sc[s], 0, 0, 0);
+            }
+            // L <= budget: rho is every token and nothing is scored
+            const int t = t0 + tl;
+            if (lane < TILE && L > budget && t < L - window && t < end) {
+#pragma unroll
+                for (int h = 0; h < GQ; ++h) P[(head0 + h) * ldp + t] = sc[h >> 2][h & 3];
+            }
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < 16; ++cc) {
+                const u32x4 kw = ktile[tl * 16 + (cc ^ (tl & 7))];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const uint2 kb = half == 0 ? make_uint2(kw.x, kw.y) : make_uint2(kw.z, kw.w);
+                    const s16x4 bq = __builtin_bit_cast(s16x4, kb);
+#pragma unroll
+                    for (int s = 0; s < SETS; ++s) {
+                        const s16x4 aq = *reinterpret_cast<const s16x4*>(&qlds[(s * 4 + (lane & 3)) * QSB + cc * 8 + half * 4]);
+                        sc[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aq, bq, sc[s], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -1079,7 +1114,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             sc[h >> 2][h & 3] = pz;
         }
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) pbuf[wave][tl][s] = sc[s];
+        for (int s = 0; s < SETS; ++s) pbuf[tl][s] = sc[s];
 #pragma unroll
         for (int h = 0; h < GQ; ++h)
 #pragma unroll
@@ -1091,7 +1126,7 @@ __global__ __launch_bounds__(ATTN_THREADS) void attn_kernel(
             unpack8(make_uint4(vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w), vf);
             f32x4 pv[SETS];
 #pragma unroll
-            for (int s = 0; s < SETS; ++s) pv[s] = pbuf[wave][i * 4 + r][s];
+            for (int s = 0; s < SETS; ++s) pv[s] = pbuf[i * 4 + r][s];
 #pragma unroll
             for (int h = 0; h < GQ; ++h)
 #pragma unroll

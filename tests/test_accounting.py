@@ -29,7 +29,10 @@ def test_closed_forms_match_the_printed_table():
 
 def test_step_bytes_adds_up_per_layer_kind():
     sched = [0, 0, 1] + [2] * 29
-    b = acc.step_bytes(sched, [32768], G=8, budget=2048, window=512)
+    fused = acc.step_bytes(sched, [32768], G=8, budget=2048, window=512)
+    assert fused["score"] == 0                                # the selection layer reads its K rows once
+    b = acc.step_bytes(sched, [32768], G=8, budget=2048, window=512, fused_select=False)
+    assert fused["total"] == b["total"] - b["score"]
     assert b["full"] == 3 * 2 * 8 * 32768 * 128 * 2
     assert b["score"] == 8 * (32768 - 512) * 128 * 2
     assert b["sparse"] == 29 * (2 * 8 * 2048 * 128 * 2 + 4 * 2048)
