@@ -37,6 +37,8 @@ def parse():
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-baseline", action="store_true")
+    ap.add_argument("--no-per-head", action="store_true",
+                    help="skip the head-to-head comparison (every head attends its own top-k instead of the unified set)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event pass (use under rocprofv3 to keep the trace to the timed steps)")
     return ap.parse_args()
@@ -63,6 +65,51 @@ def kernel_bytes(w, lens, acc):
         # the selection layer's pass: K and V once, the scores come from the same K rows
         "attn_kernel<full+score>": sum(acc.full_attn_bytes(G, L) for L in lens),
     }
+
+
+def per_head_comparison(r, w, sched, lens, steps, torch, cb, acc):
+    """The sparse layers of the step with per-head token sets (head-to-head selection, the variant the
+    paper's kernel comparison is against) next to the same layers with the unified set."""
+    sel = sched.index(1)
+    sparse_layers = [i for i, k in enumerate(sched) if k == 2]
+    idx_head = r.make_idx_head()
+    r.select_per_head(sel, idx_head)
+    r.select(sel)
+    torch.cuda.synchronize()
+    g = w.n_q_heads // w.n_kv_heads
+    n = min(w.budget, min(lens))
+    # distinct rows a KV group's heads ask for, relative to one head's list (1 = identical lists, g = disjoint)
+    grp = idx_head[:, :, :n].reshape(w.batch * w.n_kv_heads, g * n)
+    distinct = sum(int(torch.unique(row).numel()) for row in grp[: 64]) / (min(64, grp.shape[0]) * n)
+
+    def unified():
+        for i in sparse_layers:
+            r.sparse(i)
+
+    def per_head():
+        for i in sparse_layers:
+            r.sparse_per_head(i, idx_head)
+
+    t_uni = time_steps(unified, steps, 2, torch)
+    t_ph = time_steps(per_head, steps, 2, torch)
+    cb.profile_reset()
+    cb.profile_enable(True)
+    unified()
+    per_head()
+    torch.cuda.synchronize()
+    prof = cb.profile_read()
+    cb.profile_enable(False)
+    ku = prof["attn_kernel<sparse>"]
+    kp = prof["attn_kernel<per-head>"]
+    ku_us, kp_us = ku["total_ms"] * 1e3 / ku["calls"], kp["total_ms"] * 1e3 / kp["calls"]
+    b_uni = sum(acc.sparse_attn_bytes(w.n_kv_heads, w.budget, L) for L in lens)
+    b_ph = sum(acc.per_head_sparse_attn_bytes(w.n_q_heads, w.budget, L) for L in lens)
+    return {"sparse_layers": len(sparse_layers), "unified_us": round(t_uni * 1e6, 2), "per_head_us": round(t_ph * 1e6, 2),
+            "per_head_over_unified": round(t_ph / t_uni, 3),
+            "kernel_us": {"unified": round(ku_us, 3), "per_head": round(kp_us, 3), "ratio": round(kp_us / ku_us, 3)},
+            "kernel_bytes": {"unified": b_uni, "per_head": b_ph},
+            "per_head_GBs": round(b_ph / (kp_us * 1e-6) / 1e9, 1),
+            "distinct_rows_per_group_over_list": round(distinct, 3), "gqa_group": g}
 
 
 def cpu_baseline(inp, w, sched):
@@ -210,6 +257,8 @@ def main():
     if full_s is not None:
         out["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
         out["speedup_vs_full_attention"] = round(full_s / step_s, 3)
+    if not args.no_per_head and 2 in sched:
+        out["per_head_comparison"] = per_head_comparison(r, w, sched, lens, max(3, args.steps // 2), torch, cb, acc)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, w, sched)
     print(json.dumps(out), flush=True)

@@ -133,6 +133,22 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
                              const int32_t* idx, const int32_t* cnt, void* out,
                              void* ws, size_t ws_bytes, void* stream);
 
+/* Head-to-head selection and its sparse attention: the per-head variant the paper
+ * compares CUSA with (Sec. 3.2 and the generalization figure; the per-head-index
+ * kernel of the kernel-metrics table).  Every head keeps its OWN token set: its
+ * first K-W ranked picks (same scores and ranking as cusa_select) plus the last W
+ * positions; L <= K: all tokens.
+ * idx_head  device int32 [batch][n_q_heads][budget]: each head's set, ascending.
+ * cnt       device int32 [batch]: min(K, L_b), the size of every head's set.
+ * cusa_sparse_attn_per_head is Eq. 1 restricted, for head h, to idx_head[b][h][0 .. cnt[b]);
+ * nothing is shared inside a GQA group, each head loads its own K/V rows.
+ * Errors as cusa_select / cusa_sparse_attn. */
+cusa_status cusa_select_per_head(const cusa_params* params, const void* q, const cusa_kv* kv,
+                                 int32_t* idx_head, int32_t* cnt, void* ws, size_t ws_bytes, void* stream);
+cusa_status cusa_sparse_attn_per_head(const cusa_params* params, const void* q, const cusa_kv* kv,
+                                      const int32_t* idx_head, const int32_t* cnt, void* out,
+                                      void* ws, size_t ws_bytes, void* stream);
+
 /* FullAttention(q, C[:]) of Alg. 1 (Eq. 1 over all L_b tokens); also the
  * baseline the sparse path is compared with.  budget, window and topk_per_head
  * do not enter the result, but params is validated as a whole (so they must

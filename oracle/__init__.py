@@ -8,7 +8,7 @@ never does, and nothing here imports the product package.
 Arrays are numpy; bf16 tensors are ``uint16`` bit patterns.  One call handles
 one sequence given as its logical view ``q[H,d]``, ``K[G,L,d]``, ``V[G,L,d]``.
 
-Parity status: every function is pinned by CPU tests except the CHOICE of the
+Parity status: every function (the head-to-head variant included) is pinned by CPU tests except the CHOICE of the
 global-ranking reading (``rank_mode``), which is "parity unpinned" -- the paper
 defines no ranking key and prints no worked example.
 """
@@ -163,6 +163,30 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, idx: Optional[np.ndar
     _load().cusa_oracle_attention(_p(q), _p(K), _p(V), H, G, d, L, ip, n, float(sm_scale),
                                   _p(out), _p(o64))
     return (out, o64) if want_f64 else out
+
+
+def select_per_head(q: np.ndarray, K: np.ndarray, budget: int, window: int) -> np.ndarray:
+    """Head-to-head selection (the per-head variant CUSA is compared with, Sec. 3.2 and the
+    generalization figure): head h keeps its own top-(K-W) candidates plus the last W positions.
+    Returns rho_h[H, min(K, L)], every row ascending."""
+    H, L = q.shape[0], K.shape[1]
+    if L <= budget:
+        return np.tile(np.arange(L, dtype=np.int32), (H, 1))
+    Lc = L - window
+    picks = topk(scores(q, K, Lc), budget - window)                  # [H, K-W] ranked, distinct per row
+    recent = np.tile(np.arange(Lc, L, dtype=np.int32), (H, 1))
+    return np.sort(np.concatenate([picks, recent], axis=1), axis=1).astype(np.int32)
+
+
+def attention_per_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, idx_head: np.ndarray,
+                       sm_scale: Optional[float] = None) -> np.ndarray:
+    """Eq. 1 restricted, for head h, to its own token list idx_head[h]; bf16 bits out.
+    Written as H single-head calls of ``attention`` on the head's KV group."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    H, G = q.shape[0], K.shape[0]
+    g = H // G
+    return np.concatenate([attention(q[h:h + 1], K[h // g:h // g + 1], V[h // g:h // g + 1], idx_head[h], sm_scale)
+                           for h in range(H)], axis=0)
 
 
 def recall(q: np.ndarray, K: np.ndarray, idx: np.ndarray, sm_scale: Optional[float] = None):

@@ -31,6 +31,12 @@ def sparse_attn_bytes(G: int, budget: int, L: int, d: int = 128) -> int:
     return G * attn_bytes_per_kv_head(n, d) + 4 * n
 
 
+def per_head_sparse_attn_bytes(H: int, budget: int, L: int, d: int = 128) -> int:
+    """Head-to-head variant: every query head reads the K and V rows of its own list."""
+    n = min(budget, L)
+    return H * (attn_bytes_per_kv_head(n, d) + 4 * n)
+
+
 def score_bytes(G: int, L: int, budget: int, window: int, d: int = 128) -> int:
     """K rows of the candidate range [0, L-W), read once; nothing when the budget covers L."""
     if L <= budget:

@@ -22,6 +22,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_LAUNCH = rang
 
 EXPORTS = [
     "cusa_workspace_bytes", "cusa_workspace_layout", "cusa_select", "cusa_sparse_attn",
+    "cusa_select_per_head", "cusa_sparse_attn_per_head",
     "cusa_full_attn", "cusa_decode_step", "cusa_strerror", "cusa_profile_num_kernels",
     "cusa_profile_kernel_name", "cusa_profile_enable", "cusa_profile_reset", "cusa_profile_read",
 ]
@@ -74,9 +75,12 @@ def load():
     lib.cusa_workspace_layout.argtypes = [P(CusaParams), i32, P(CusaWsLayout)]
     lib.cusa_select.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, sz, vp]
     lib.cusa_sparse_attn.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, vp, sz, vp]
+    lib.cusa_select_per_head.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, sz, vp]
+    lib.cusa_sparse_attn_per_head.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, vp, sz, vp]
     lib.cusa_full_attn.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, sz, vp]
     lib.cusa_decode_step.argtypes = [P(CusaParams), i32, P(i32), P(vp), P(CusaKv), P(vp), vp, vp, vp, sz, vp]
     for name in ("cusa_workspace_bytes", "cusa_workspace_layout", "cusa_select", "cusa_sparse_attn",
+                 "cusa_select_per_head", "cusa_sparse_attn_per_head",
                  "cusa_full_attn", "cusa_decode_step", "cusa_profile_read"):
         getattr(lib, name).restype = ctypes.c_int
     lib.cusa_strerror.argtypes = [ctypes.c_int]
@@ -165,6 +169,19 @@ def sparse_attn(params: CusaParams, q, kv: KvCache, idx, cnt, out, ws):
     d = kv.desc()
     _check(load().cusa_sparse_attn(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx), _ptr(cnt),
                                    _ptr(out), _ptr(ws), ws.numel(), _stream()), "cusa_sparse_attn")
+
+
+def select_per_head(params: CusaParams, q, kv: KvCache, idx_head, cnt, ws):
+    """idx_head: int32 [B, H, budget]; every head keeps its own picks (head-to-head selection)."""
+    d = kv.desc()
+    _check(load().cusa_select_per_head(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx_head), _ptr(cnt),
+                                       _ptr(ws), ws.numel(), _stream()), "cusa_select_per_head")
+
+
+def sparse_attn_per_head(params: CusaParams, q, kv: KvCache, idx_head, cnt, out, ws):
+    d = kv.desc()
+    _check(load().cusa_sparse_attn_per_head(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx_head), _ptr(cnt),
+                                            _ptr(out), _ptr(ws), ws.numel(), _stream()), "cusa_sparse_attn_per_head")
 
 
 def full_attn(params: CusaParams, q, kv: KvCache, out, ws):

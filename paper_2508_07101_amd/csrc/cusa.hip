@@ -18,10 +18,10 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
-                                             "attn_kernel<full+score>"};
+                                             "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -251,10 +251,21 @@ void launch_attn_partial(const AttnArgs& a) {
     const int kid = SPARSE ? KID_ATTN_SPARSE : SCORE ? KID_ATTN_SELECT : KID_ATTN_FULL;
     if (a.paged)
         launch(kid, attn_kernel<GQ, TI, SPARSE, true, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, a.view);
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, 0, a.view);
     else
         launch(kid, attn_kernel<GQ, TI, SPARSE, false, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, a.view);
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, 0, a.view);
+}
+
+// Sparse attention with one token list per query head: grid.y counts query heads.
+template <int TI>
+void launch_attn_per_head(const AttnArgs& a, int H, int hshift) {
+    if (a.paged)
+        launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, true, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, nullptr, 0, 0, hshift, a.view);
+    else
+        launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, false, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, nullptr, 0, 0, hshift, a.view);
 }
 
 template <int GQ, bool SPARSE>
@@ -312,6 +323,38 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     return launch_status();
 }
 
+// Sparse attention over idx_head [B][H][budget]: every query head is its own "group".
+cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cusa_kv* kv, const int32_t* idx_head,
+                                   const int32_t* cnt, void* out, void* ws, const WsLayout& w, hipStream_t s) {
+    const int H = p->n_q_heads, g = H / p->n_kv_heads;
+    const int n_max = p->budget < kv->max_seq_len ? p->budget : kv->max_seq_len;
+    const AttnPlan pl = plan_attn(n_max, p->batch * H, 1);
+    if (pl.n_splits > w.max_splits) return CUSA_ERR_WORKSPACE_TOO_SMALL;
+    AttnArgs a;
+    a.paged = kv->layout == CUSA_KV_PAGED;
+    a.grid = dim3(pl.n_splits, H, p->batch);
+    a.s = s;
+    a.view = make_view(p, kv);
+    a.q = static_cast<const uint16_t*>(q);
+    a.idx = idx_head;
+    a.cnt = cnt;
+    a.budget = p->budget;
+    a.scale = p->sm_scale * 1.4426950408889634f;
+    a.pa = ws_ptr<float>(ws, w.part_acc);
+    a.pm = ws_ptr<float>(ws, w.part_ml);
+    a.out = static_cast<uint16_t*>(out);
+    a.n_splits = pl.n_splits;
+    a.chunk = pl.chunk;
+    const int hshift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
+    if (pl.ti == 8) launch_attn_per_head<8>(a, H, hshift);
+    else launch_attn_per_head<4>(a, H, hshift);
+    if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+    if (pl.n_splits > 1)
+        launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, a.pa, a.pm, a.out, cnt, p->budget, pl.n_splits,
+               pl.chunk, H);
+    return launch_status();
+}
+
 // LDS beyond 48 KB per workgroup has to be granted per kernel; remembered per kernel so the
 // runtime is asked once.
 
@@ -360,8 +403,9 @@ void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const
 }
 
 // scores_ready: P was already written by the layer's attention pass (cusa_decode_step).
+// per_head: idx is [B][H][budget], every head keeps its own first K-W picks (head-to-head selection).
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
-                       const WsLayout& w, hipStream_t s, bool scores_ready = false) {
+                       const WsLayout& w, hipStream_t s, bool scores_ready = false, bool per_head = false) {
     const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
     const KvView view = make_view(p, kv);
     const bool paged = kv->layout == CUSA_KV_PAGED;
@@ -404,6 +448,13 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
         // the union's bitmap over candidate positions lives in LDS
         const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
         const size_t bitmap = ((((size_t)lc_max + 31) / 32) * 4 + 255) & ~(size_t)255;
+        if (per_head) {
+            if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
+                return CUSA_ERR_LAUNCH;
+            launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(H, B), SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H,
+                   w.k, p->budget, p->window);
+            return launch_status();
+        }
         if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel), bitmap)) return CUSA_ERR_LAUNCH;
         launch(KID_UNION, union_kernel, B, SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H, w.k, p->budget,
                p->window);
@@ -460,6 +511,30 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
     return run_attention<true>(params, q, kv, idx, cnt, n_max, out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_select_per_head(const cusa_params* params, const void* q, const cusa_kv* kv, int32_t* idx_head,
+                                 int32_t* cnt, void* ws, size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx_head || !cnt || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    if ((st = check_select_length(params, kv)) != CUSA_OK) return st;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    return run_select(params, q, kv, idx_head, cnt, ws, w, static_cast<hipStream_t>(stream), false, true);
+}
+
+cusa_status cusa_sparse_attn_per_head(const cusa_params* params, const void* q, const cusa_kv* kv,
+                                      const int32_t* idx_head, const int32_t* cnt, void* out, void* ws,
+                                      size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx_head || !cnt || !out || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    return run_attention_per_head(params, q, kv, idx_head, cnt, out, ws, w, static_cast<hipStream_t>(stream));
 }
 
 cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv, void* out, void* ws,

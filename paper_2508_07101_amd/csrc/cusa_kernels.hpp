@@ -846,6 +846,57 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     if (tid == 0) cnt[b] = n_take + window;
 }
 
+// Head-to-head selection (the per-head variant the paper compares with, Sec. 3.2 and the
+// generalization figure): head h of sequence b keeps ITS OWN first K-W ranked picks plus the window.
+// One workgroup per (head, sequence): the picks (distinct positions) are set in an LDS bitmap over
+// the candidate positions and emitted in ascending order like the unified set.
+// idx_head [B][H][budget]; cnt[b] = min(K, L_b) is the same for every head.
+__global__ __launch_bounds__(SEL_THREADS) void per_head_rho_kernel(const int32_t* __restrict__ rho_head,
+                                                                    const int32_t* __restrict__ seq_lens,
+                                                                    int32_t* __restrict__ idx_head,
+                                                                    int32_t* __restrict__ cnt, int H, int k,
+                                                                    int budget, int window) {
+    extern __shared__ uint32_t bits[];                // ceil(Lc / 32) words
+    __shared__ int scratch[SEL_WAVES + 1];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int L = seq_lens[b];
+    int32_t* __restrict__ out = idx_head + ((int64_t)b * H + h) * budget;
+    if (L <= budget) {
+        for (int t = tid; t < L; t += SEL_THREADS) out[t] = t;
+        if (tid == 0 && h == 0) cnt[b] = L;
+        return;
+    }
+    const int Lc = L - window;
+    const int k_eff = k < Lc ? k : Lc;
+    const int n_hist = min(budget - window, k_eff);   // = K - W: k >= K - W and Lc > K - W here
+    const int n_words = (Lc + 31) >> 5;
+    for (int i = tid; i < n_words; i += SEL_THREADS) bits[i] = 0u;
+    __syncthreads();
+    const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H + h;   // rank j at rho[j * H]
+    for (int j = tid; j < n_hist; j += SEL_THREADS) {
+        const int t = rho[(int64_t)j * H];
+        if ((uint32_t)t < (uint32_t)Lc) atomicOr(&bits[t >> 5], 1u << (t & 31));
+    }
+    __syncthreads();
+    const int wpt = (n_words + SEL_THREADS - 1) / SEL_THREADS;
+    const int w_lo = tid * wpt, w_hi = (w_lo + wpt < n_words) ? w_lo + wpt : n_words;
+    int mine = 0;
+    for (int i = w_lo; i < w_hi; ++i) mine += __popc(bits[i]);
+    int total;
+    int off = block_scan_excl(mine, scratch, &total);
+    for (int i = w_lo; i < w_hi; ++i) {
+        uint32_t word = bits[i];
+        while (word) {
+            const int bpos = __ffs(word) - 1;
+            if (off < n_hist) out[off] = i * 32 + bpos;
+            ++off;
+            word &= word - 1;
+        }
+    }
+    for (int j = tid; j < window; j += SEL_THREADS) out[n_hist + j] = L - window + j;
+    if (tid == 0 && h == 0) cnt[b] = n_hist + window;
+}
+
 // ---------------------------------------------------------------- attention (split-K flash-decode)
 //
 // grid (n_splits, G, B), 256 threads.  A workgroup owns a contiguous run of the
@@ -940,13 +991,19 @@ __device__ __forceinline__ void wave_lds_sync() {
 // is read once for both (Alg. 1 computes the layer's output and P from the same K).  q.k then runs
 // as the k = 1 MFMA chain of score_kernel -- the pinned left-to-right binary32 sum -- instead of
 // the k = 4 bf16 MFMA, and the softmax uses those same values.
-template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false>
+//
+// PER_HEAD (sparse, GQ = 1): every query head attends its own token list idx[b][head][0 .. cnt[b])
+// -- the head-to-head selection the paper compares with (Sec. 3.2, the generalization figure) --
+// so a workgroup serves one query head, blockIdx.y counts query heads (G of them) and head y reads
+// KV head y >> hshift.  Nothing is shared inside a GQA group: each head fetches its own rows.
+template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_HEAD = false>
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
     const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
     float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ P,
-    int64_t ldp, int window, KvView kv) {
+    int64_t ldp, int window, int hshift, KvView kv) {
     static_assert(!(SCORE && SPARSE), "scores are emitted by the pass over all tokens");
+    static_assert(!PER_HEAD || (SPARSE && GQ == 1), "per-head token lists: one query head per workgroup");
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one MFMA accumulator each
@@ -967,12 +1024,13 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
-    const int kvh = blockIdx.y, b = blockIdx.z, H = G * GQ;
-    const int split = (int)((blockIdx.x + kvh + G * b) % (unsigned)n_splits);
+    const int gy = blockIdx.y, b = blockIdx.z, H = G * GQ;
+    const int kvh = PER_HEAD ? gy >> hshift : gy;
+    const int split = (int)((blockIdx.x + gy + G * b) % (unsigned)n_splits);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, c = lane & 15;
     const int begin = split * chunk;
-    const int32_t* __restrict__ my_idx = idx + (int64_t)b * budget;
-    const int64_t head0 = (int64_t)b * H + kvh * GQ;     // first query head of this group
+    const int32_t* __restrict__ my_idx = idx + (PER_HEAD ? (int64_t)b * G + gy : (int64_t)b) * budget;
+    const int64_t head0 = (int64_t)b * H + gy * GQ;      // first query head of this group
     // The token indices of a tile are fetched one tile ahead, the first ones before the token
     // count is known: the row of idx has `budget` entries, so a read clamped to budget - 1 stays
     // inside it, and entries past the count are masked below like every row past the run's end.

@@ -53,6 +53,18 @@ class StepRunner:
         cb.sparse_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt,
                        self.outs[layer_pos], self.ws)
 
+    # head-to-head variant: every head its own token set, idx_head [B, H, budget]
+    def make_idx_head(self) -> torch.Tensor:
+        w = self.inp.workload
+        return torch.full((w.batch, w.n_q_heads, w.budget), -1, dtype=torch.int32, device=self.idx.device)
+
+    def select_per_head(self, layer_pos: int, idx_head: torch.Tensor):
+        cb.select_per_head(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], idx_head, self.cnt, self.ws)
+
+    def sparse_per_head(self, layer_pos: int, idx_head: torch.Tensor):
+        cb.sparse_attn_per_head(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], idx_head, self.cnt,
+                                self.outs[layer_pos], self.ws)
+
     def full(self, layer_pos: int):
         cb.full_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.ws)
 

@@ -93,6 +93,21 @@ def test_null_and_misshapen_arguments_are_rejected_before_any_launch():
     assert lib.cusa_sparse_attn(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
 
 
+def test_per_head_entry_points_reject_bad_arguments_before_any_launch():
+    lib = cb.load()
+    p = cb.make_params(1, 32, 8, 2048, 512)
+    kv = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 128, None, 0, 0, 0, 0x3000, 4096)
+    fake = ctypes.c_void_p(0x10000)
+    assert lib.cusa_select_per_head(ctypes.byref(p), fake, ctypes.byref(kv), None, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_select_per_head(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    lng = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 2_000_000 * 128, 128, None, 0, 0, 0, 0x3000, 2_000_000)
+    assert lib.cusa_select_per_head(ctypes.byref(p), fake, ctypes.byref(lng), fake, fake, fake, 1 << 40, None) == cb.ERR_UNSUPPORTED
+    assert lib.cusa_sparse_attn_per_head(ctypes.byref(p), fake, ctypes.byref(kv), fake, None, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_sparse_attn_per_head(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    bad = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 64, None, 0, 0, 0, 0x3000, 4096)
+    assert lib.cusa_sparse_attn_per_head(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+
+
 def test_decode_step_rejects_sparse_before_select_and_unknown_kinds():
     lib = cb.load()
     p = cb.make_params(1, 32, 8, 2048, 512)

@@ -279,6 +279,47 @@ def test_standalone_entry_points_match_the_oracle(H, paged, L):
     check_attention(inp, r, 1, LAYER_SPARSE, seqs)
 
 
+@pytest.mark.parametrize("H,paged,lengths", [(8, False, (1500, 900, 1211)), (16, True, (100, 1500, 257)),
+                                             (32, False, (1500, 256, 1033)), (64, True, (1400, 1500, 700)),
+                                             (32, True, (9000, 300, 7001))])
+def test_per_head_selection_and_attention_match_the_oracle(H, paged, lengths):
+    """Head-to-head variant: every head its own top-(K-W) + window, and sparse attention over it."""
+    w = small(f"perhead{H}", n_q_heads=H, n_kv_heads=8, batch=len(lengths), seq_len=max(lengths), lengths=lengths,
+              paged=paged, n_planted=5)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    _say(f"{w.name}: per-head select + sparse attention, lens {inp.seq_lens_host}")
+    idx_head = r.make_idx_head()
+    r.select_per_head(0, idx_head)
+    r.sparse_per_head(1, idx_head)
+    torch.cuda.synchronize()
+    got_idx, got_cnt = idx_head.cpu().numpy(), r.cnt.cpu().numpy()
+    out = bf16_bits(r.outs[1])
+    for b in range(w.batch):
+        q, K, _ = host_view(inp, 0, b)
+        rho_h = oracle.select_per_head(q, K, w.budget, w.window)
+        assert got_cnt[b] == rho_h.shape[1] == min(w.budget, inp.seq_lens_host[b])
+        assert (got_idx[b, :, : got_cnt[b]] == rho_h).all(), f"per-head sets differ, seq {b}"
+        q, K, V = host_view(inp, 1, b)
+        assert_close_bf16(out[b], oracle.attention_per_head(q, K, V, rho_h), f"per-head attention seq {b}")
+
+
+def test_per_head_attention_with_one_shared_list_equals_the_unified_kernel():
+    w = small("perhead_shared", batch=2, seq_len=3000, budget=512, window=128)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.select(0)
+    r.sparse(1)
+    torch.cuda.synchronize()
+    want = r.outs[1].clone()
+    idx_head = r.idx[:, None, :].expand(-1, w.n_q_heads, -1).contiguous()
+    r.outs[1].zero_()
+    r.sparse_per_head(1, idx_head)
+    torch.cuda.synchronize()
+    # same tokens, same order of accumulation inside a tile; the split of the list over workgroups differs
+    torch.testing.assert_close(r.outs[1].float(), want.float(), atol=2e-2, rtol=1e-2)
+
+
 def test_strided_contiguous_cache_view():
     """K/V given as [B, L, G, d] storage viewed as [B, G, L, d] (token stride G*d)."""
     w = small("strided", batch=2, seq_len=900)

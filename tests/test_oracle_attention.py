@@ -116,3 +116,27 @@ def test_recall_definition():
         p /= p.sum()
         np.testing.assert_allclose(r[h], p[idx].sum(), rtol=1e-12)
     np.testing.assert_allclose(oracle.recall(q, K, np.arange(L, dtype=np.int32)), 1.0, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- head-to-head (per-head) variant
+
+def test_per_head_attention_with_one_shared_list_is_the_unified_sparse_attention():
+    rng = np.random.default_rng(71)
+    H, G, L = 8, 2, 90
+    q, K, V = rand_qkv(rng, H, G, L)
+    idx = np.sort(rng.choice(L, size=20, replace=False)).astype(np.int32)
+    got = oracle.attention_per_head(q, K, V, np.tile(idx, (H, 1)))
+    np.testing.assert_array_equal(got, oracle.attention(q, K, V, idx))
+
+
+def test_per_head_attention_is_dense_attention_on_each_heads_gathered_rows():
+    """Head h with list T_h must equal dense attention of q_h over K[h // g, T_h], V[h // g, T_h]."""
+    rng = np.random.default_rng(72)
+    H, G, L, n = 6, 3, 70, 17
+    q, K, V = rand_qkv(rng, H, G, L)
+    idx_head = np.stack([np.sort(rng.choice(L, size=n, replace=False)) for _ in range(H)]).astype(np.int32)
+    got = bits_to_f64(oracle.attention_per_head(q, K, V, idx_head))
+    for h in range(H):
+        kv = h // (H // G)
+        ref = dense_attention_f64(q[h:h + 1], K[kv:kv + 1, idx_head[h]], V[kv:kv + 1, idx_head[h]])[0]
+        np.testing.assert_allclose(got[h], ref, rtol=2 ** -8, atol=1e-30)      # bf16 rounding of the output

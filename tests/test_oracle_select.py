@@ -219,3 +219,27 @@ def test_paged_view_resolution():
     for kv in range(G):
         for t in range(L):
             np.testing.assert_array_equal(view[kv, t], pool[bt[t // page], kv, t % page])
+
+
+# ---------------------------------------------------------------- head-to-head (per-head) variant
+
+def test_per_head_selection_is_each_heads_own_topk_plus_window():
+    rng = np.random.default_rng(61)
+    H, G, L, K, W = 8, 2, 400, 64, 16
+    q, Kc, _ = rand_qkv(rng, H, G, L)
+    rho_h = oracle.select_per_head(q, Kc, K, W)
+    assert rho_h.shape == (H, K) and (np.diff(rho_h, axis=1) > 0).all()
+    P = oracle.scores(q, Kc, L - W)
+    for h in range(H):
+        want = sorted(np.argsort(-P[h], kind="stable")[: K - W].tolist() + list(range(L - W, L)))
+        assert rho_h[h].tolist() == want
+    # the unified set takes every token from some head's own set
+    rho = oracle.select(q, Kc, K, W)
+    assert set(rho) <= set(rho_h.ravel())
+
+
+def test_per_head_selection_with_one_head_is_the_unified_selection():
+    rng = np.random.default_rng(62)
+    q, Kc, _ = rand_qkv(rng, 1, 1, 250)
+    np.testing.assert_array_equal(oracle.select_per_head(q, Kc, 48, 12)[0], oracle.select(q, Kc, 48, 12))
+    np.testing.assert_array_equal(oracle.select_per_head(q, Kc, 300, 12)[0], np.arange(250))   # budget covers L
