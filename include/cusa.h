@@ -46,10 +46,13 @@ typedef enum { CUSA_LAYER_FULL = 0, CUSA_LAYER_SELECT = 1, CUSA_LAYER_SPARSE = 2
 typedef enum { CUSA_KV_CONTIGUOUS = 0, CUSA_KV_PAGED = 1 } cusa_kv_layout;
 
 /* Reading of "globally ranked" in Sec. 3.2 (the paper names no ranking key).
- * FIRST_OCCURRENCE: flatten the per-head ranked lists rank-major (all rank-0
- * picks in head order, then all rank-1 picks, ...), drop repeats, keep the
- * first K-W tokens.  The other two are reserved values: this build returns
- * CUSA_ERR_UNSUPPORTED for them. */
+ * FIRST_OCCURRENCE (the default reading): flatten the per-head ranked lists
+ * rank-major (all rank-0 picks in head order, then all rank-1 picks, ...), drop
+ * repeats, keep the first K-W tokens.
+ * VOTES: rank the distinct picks by the number of heads proposing them
+ * (descending), then by the best rank any head gave them, then by position.
+ * MAX_SCORE: rank them by the largest score among the proposing heads
+ * (descending), then by position.  Both keep the first K-W of that order. */
 typedef enum { CUSA_RANK_FIRST_OCCURRENCE = 0, CUSA_RANK_VOTES = 1, CUSA_RANK_MAX_SCORE = 2 } cusa_rank_mode;
 
 /* Problem statement of Alg. 1 ("token budget K, static ratio r"), host memory. */
@@ -94,7 +97,9 @@ typedef struct {
  *   scores    float  [batch][n_q_heads][ld_scores]   P = q.K^T over [0, L_b-W)
  *   rho_head  int32  [batch][k][n_q_heads]           ranked picks, RANK-MAJOR:
  *             entry (b, j, h) is head h's rank-j pick; valid for j < min(k, L_b-W)
- * Both are defined only for sequences with L_b > K. */
+ * Both are defined only for sequences with L_b > K.  (With rank_mode VOTES or
+ * MAX_SCORE the workspace also holds one ranking key per candidate position and the
+ * unified ranked list; they are internal.) */
 typedef struct {
     size_t  scores_offset;
     int64_t ld_scores;
@@ -120,7 +125,7 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
  * q    device bf16 [batch][n_q_heads][128], this layer's query.
  * idx  device int32 [batch][budget]: rho ascending; entries >= cnt[b] unspecified.
  * cnt  device int32 [batch]: |rho| = min(K, L_b).
- * Errors: INVALID_ARG, UNSUPPORTED (rank_mode; max_seq_len - W above 1 179 648,
+ * Errors: INVALID_ARG, UNSUPPORTED (max_seq_len - W above 1 179 648,
  * the positions the selection's on-chip bitmap covers), WORKSPACE_TOO_SMALL, LAUNCH. */
 cusa_status cusa_select(const cusa_params* params, const void* q, const cusa_kv* kv,
                         int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream);

@@ -18,10 +18,11 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
-                                             "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel"};
+                                             "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
+                                             "rank_aggregate_kernel"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -92,10 +93,9 @@ cusa_status check_params(const cusa_params* p, bool need_budget) {
         if (p->budget < 1 || p->window < 0 || p->window > p->budget) return CUSA_ERR_INVALID_ARG;
         if (p->topk_per_head < 0) return CUSA_ERR_INVALID_ARG;
         if (p->n_sink != 0) return CUSA_ERR_UNSUPPORTED;
-        if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {
-            if (p->rank_mode == CUSA_RANK_VOTES || p->rank_mode == CUSA_RANK_MAX_SCORE) return CUSA_ERR_UNSUPPORTED;
+        if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE && p->rank_mode != CUSA_RANK_VOTES &&
+            p->rank_mode != CUSA_RANK_MAX_SCORE)
             return CUSA_ERR_INVALID_ARG;
-        }
         const int k = resolved_k(p);
         if (k < p->budget - p->window) return CUSA_ERR_INVALID_ARG;
         if (k > 8192) return CUSA_ERR_UNSUPPORTED;
@@ -175,7 +175,7 @@ AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
 }
 
 struct WsLayout {
-    size_t scores, rho_head, part_acc, part_ml, total;
+    size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -198,6 +198,11 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);
     w.part_acc = off;  off += align256((size_t)(B * H * w.max_splits * D) * 4);
     w.part_ml = off;   off += align256((size_t)(B * H * w.max_splits * 2) * 4);
+    w.agg = w.rho_rank = off;
+    if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {   // per-position ranking keys and the unified ranked list
+        w.agg = off;       off += align256((size_t)(B * 2 * w.ldp) * 4);
+        w.rho_rank = off;  off += align256((size_t)(B * (p->budget - p->window + 1)) * 4);
+    }
     w.total = off;
     return w;
 }
@@ -374,11 +379,11 @@ bool allow_dynamic_lds(const void* fn, size_t bytes) {
 
 template <int ITEMS, int MTOP>
 cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                          int32_t* rho_head, int H, int k, int budget, int window) {
+                          int32_t* rho_head, int H, int k, int budget, int window, int raw) {
     const size_t shmem = ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
     if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
         return CUSA_ERR_LAUNCH;
-    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
+    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
     return launch_status();
 }
 
@@ -386,11 +391,24 @@ cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp,
 // candidates kept for the lower bound.
 template <int ITEMS>
 cusa_status launch_topk(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                        int32_t* rho_head, int H, int k, int budget, int window) {
-    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
-    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
-    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
-    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window);
+                        int32_t* rho_head, int H, int k, int budget, int window, int raw) {
+    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+}
+
+// Ranked top-k of every row of P: rows (b, h) of length L_b - W, output rank-major out[b][j][h].
+// raw: the rows hold uint32 keys instead of scores.
+cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
+                     int32_t* out, int k, int budget, int window, int raw) {
+    const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
+    const dim3 tg(H, B);
+    if (items <= 4) return launch_topk<4>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
+    if (items <= 8) return launch_topk<8>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
+    if (items <= 16) return launch_topk<16>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
+    if (items <= 32) return launch_topk<32>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
+    return launch_topk<0>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
 }
 
 template <int GQ>
@@ -432,22 +450,33 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
             }
             if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         }
-        const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
-        cusa_status st;
-        {
-            const dim3 tg(H, B);
-            if (items <= 4) st = launch_topk<4>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
-            else if (items <= 8) st = launch_topk<8>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
-            else if (items <= 16) st = launch_topk<16>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
-            else if (items <= 32) st = launch_topk<32>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
-            else st = launch_topk<0>(tg, s, P, w.ldp, kv->seq_lens, rho_head, H, w.k, p->budget, p->window);
-        }
+        cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0);
         if (st != CUSA_OK) return st;
     }
     {
         // the union's bitmap over candidate positions lives in LDS
         const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
         const size_t bitmap = ((((size_t)lc_max + 31) / 32) * 4 + 255) & ~(size_t)255;
+        const int n_hist = p->budget - p->window;
+        if (!per_head && p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {
+            // votes / max-score readings: one key per candidate position, the K-W best positions by key
+            // (the same ranked top-k kernel, one row per sequence), then the ascending emission
+            int32_t* rho_rank = ws_ptr<int32_t>(ws, w.rho_rank);
+            if (n_hist > 0 && kv->max_seq_len > p->budget) {
+                uint32_t* agg = ws_ptr<uint32_t>(ws, w.agg);
+                launch(KID_RANK_AGG, rank_aggregate_kernel, B, SEL_THREADS, 0, s, rho_head, P, w.ldp, kv->seq_lens, agg, w.ldp,
+                       H, w.k, p->budget, p->window, p->rank_mode == CUSA_RANK_MAX_SCORE ? 1 : 0);
+                if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+                const cusa_status st = run_topk(lc_max, B, 1, s, reinterpret_cast<const float*>(agg), 2 * w.ldp, kv->seq_lens,
+                                                rho_rank, n_hist, p->budget, p->window, 1);
+                if (st != CUSA_OK) return st;
+            }
+            if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
+                return CUSA_ERR_LAUNCH;
+            launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(1, B), SEL_THREADS, bitmap, s, rho_rank, kv->seq_lens, idx, cnt, 1,
+                   n_hist, p->budget, p->window);
+            return launch_status();
+        }
         if (per_head) {
             if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
                 return CUSA_ERR_LAUNCH;

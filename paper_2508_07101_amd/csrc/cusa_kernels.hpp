@@ -419,7 +419,7 @@ template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
-                                                            int budget, int window) {
+                                                            int budget, int window, int raw_keys) {
     constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
     constexpr int CAP = topk_list_cap(ITEMS, MTOP);
     extern __shared__ uint64_t sort_buf[];            // NSORT composites (aliases the histogram), then CAP list entries
@@ -437,12 +437,15 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
 
     CUSA_TRACE_POINT(0);
+    // raw_keys: the row already holds order-preserving uint32 keys (the aggregated ranking keys of
+    // the votes / max-score readings) instead of binary32 scores
+    auto key_of = [raw_keys](float v) { return raw_keys ? __float_as_uint(v) : score_key(v); };
     uint32_t keys[ITEMS > 0 ? ITEMS : 1];
     if constexpr (ITEMS > 0) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int t = i * SEL_THREADS + threadIdx.x;
-            const uint32_t kv_ = score_key(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
+            const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
             keys[i] = t < Lc ? kv_ : 0u;
         }
     }
@@ -458,7 +461,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 #pragma unroll
                 for (int u = 0; u < 32; ++u) {
                     const int t = t0 + u * SEL_THREADS + threadIdx.x;
-                    const uint32_t kv_ = score_key(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
+                    const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
                     kk[u] = t < Lc ? kv_ : 0u;
                 }
 #pragma unroll
@@ -844,6 +847,57 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     CUSA_TRACE_POINT(4);
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;
+}
+
+// Aggregation for the other two readings of "globally ranked" (Sec. 3.2 names no ranking key):
+// one key per candidate position, larger = better, 0 = proposed by no head.
+//   votes     : (number of proposing heads) << 13 | (8191 - best rank among them)
+//   max score : score_key of the largest score among the proposing heads
+// The unified list is then the top K-W positions by (key descending, position ascending), which the
+// per-head top-k kernel computes from the key row (raw_keys).  One workgroup per sequence walks
+// the H * k_eff picks; key rows live in the workspace: agg[b][0][.] keys, agg[b][1][.] best ranks.
+constexpr int RANK_VOTES_SHIFT = 13;                  // ranks are below 8192
+
+__global__ __launch_bounds__(SEL_THREADS) void rank_aggregate_kernel(const int32_t* __restrict__ rho_head,
+                                                                      const float* __restrict__ P, int64_t ldp,
+                                                                      const int32_t* __restrict__ seq_lens,
+                                                                      uint32_t* __restrict__ agg, int64_t ld_agg, int H,
+                                                                      int k, int budget, int window, int by_score) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int L = seq_lens[b];
+    if (L <= budget) return;
+    const int Lc = L - window;
+    const int k_eff = k < Lc ? k : Lc;
+    const int S = k_eff * H;
+    uint32_t* const key = agg + (int64_t)b * 2 * ld_agg;
+    uint32_t* const best = key + ld_agg;
+    for (int t = tid; t < Lc; t += SEL_THREADS) {
+        key[t] = 0u;
+        best[t] = 0u;
+    }
+    __threadfence();
+    __syncthreads();
+    const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
+    for (int s = tid; s < S; s += SEL_THREADS) {
+        const int j = s / H, h = s - j * H;
+        const int t = rho[s];
+        if ((uint32_t)t >= (uint32_t)Lc) continue;    // never: a pick is a candidate position
+        if (by_score) {
+            atomicMax(&key[t], score_key(P[((int64_t)b * H + h) * ldp + t]));
+        } else {
+            atomicAdd(&key[t], 1u << RANK_VOTES_SHIFT);
+            atomicMax(&best[t], (uint32_t)(8191 - j));
+        }
+    }
+    if (by_score) return;
+    __threadfence();
+    __syncthreads();
+    for (int t = tid; t < Lc; t += SEL_THREADS) {
+        // the atomics above were carried out in L2: read there, not in this CU's L1
+        const uint32_t v = __hip_atomic_load(&key[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t r = __hip_atomic_load(&best[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v) key[t] = v | r;
+    }
 }
 
 // Head-to-head selection (the per-head variant the paper compares with, Sec. 3.2 and the

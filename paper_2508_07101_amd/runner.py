@@ -11,10 +11,10 @@ from . import binding as cb
 from .workloads import Inputs
 
 
-def params_of(inp: Inputs) -> cb.CusaParams:
+def params_of(inp: Inputs, rank_mode: int = cb.RANK_FIRST_OCCURRENCE) -> cb.CusaParams:
     w = inp.workload
     return cb.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.budget, w.window, w.topk_per_head,
-                          head_dim=w.head_dim)
+                          head_dim=w.head_dim, rank_mode=rank_mode)
 
 
 def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:
@@ -25,13 +25,13 @@ def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:
 class StepRunner:
     """One decode step (attention part of Alg. 1) over ``inp.layers`` with ``schedule``."""
 
-    def __init__(self, inp: Inputs, schedule: Optional[List[int]] = None):
+    def __init__(self, inp: Inputs, schedule: Optional[List[int]] = None, rank_mode: int = cb.RANK_FIRST_OCCURRENCE):
         w = inp.workload
         self.inp = inp
         self.schedule = list(w.schedule if schedule is None else schedule)
         assert len(self.schedule) == len(inp.layers)
         dev = inp.seq_lens.device
-        self.params = params_of(inp)
+        self.params = params_of(inp, rank_mode)
         self.max_len = max(inp.seq_lens_host)
         self.kvs = [kv_of(inp, i) for i in range(len(inp.layers))]
         self.outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)

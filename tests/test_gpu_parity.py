@@ -28,7 +28,7 @@ def small(name="t", **kw):
     return wl.Workload(**base)
 
 
-def check_select(inp, runner, layer_pos, seqs=None, check_scores=True):
+def check_select(inp, runner, layer_pos, seqs=None, check_scores=True, rank_mode=0):
     w = inp.workload
     torch.cuda.synchronize()
     idx = runner.idx.cpu().numpy()
@@ -37,7 +37,7 @@ def check_select(inp, runner, layer_pos, seqs=None, check_scores=True):
     for b in (range(w.batch) if seqs is None else seqs):
         q, K, _ = host_view(inp, layer_pos, b)
         L = inp.seq_lens_host[b]
-        rho, rho_head, P = oracle.select(q, K, w.budget, w.window, w.topk_per_head, return_all=True)
+        rho, rho_head, P = oracle.select(q, K, w.budget, w.window, w.topk_per_head, rank_mode, return_all=True)
         if L > w.budget:
             Lc = L - w.window
             if check_scores:
@@ -127,12 +127,12 @@ def test_edge_lengths_and_budgets(L, K, W, k):
         check_attention(inp, r, i, kind)
 
 
-def _with_keys(w, fn):
+def _with_keys(w, fn, rank_mode=0):
     inp = wl.make_inputs(w, DEV)
     fn(inp.layers[0].k)
-    r = StepRunner(inp)
+    r = StepRunner(inp, rank_mode=rank_mode)
     r.run()
-    check_select(inp, r, 0)
+    check_select(inp, r, 0, rank_mode=rank_mode)
     return inp, r
 
 
@@ -318,6 +318,39 @@ def test_per_head_attention_with_one_shared_list_equals_the_unified_kernel():
     torch.cuda.synchronize()
     # same tokens, same order of accumulation inside a tile; the split of the list over workgroups differs
     torch.testing.assert_close(r.outs[1].float(), want.float(), atol=2e-2, rtol=1e-2)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=32, batch=3, seq_len=1500, lengths=(1500, 200, 1033)),
+    dict(n_q_heads=64, batch=2, seq_len=2600, paged=True, lowrank=4, budget=512, window=128, topk_per_head=700),
+    dict(n_q_heads=8, batch=2, seq_len=9000, min_seq_len=7000, budget=1024, window=0),
+    dict(n_q_heads=16, batch=2, seq_len=700, budget=128, window=128),
+], ids=["ragged", "correlated_paged_widek", "long_no_window", "window_only"])
+def test_votes_and_max_score_rankings_match_the_oracle(mode, kw):
+    """The other two readings of the global ranking (number of proposing heads; best proposing score)."""
+    base = dict(n_kv_heads=8, n_planted=6)
+    base.update(kw)
+    w = small(f"rank{mode}", **base)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp, rank_mode=mode)
+    _say(f"{w.name}: rank mode {mode}, decode step then stand-alone select, lens {inp.seq_lens_host}")
+    r.run()
+    check_select(inp, r, 0, rank_mode=mode)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+    step_idx = r.idx.clone()
+    r.idx.fill_(-1)
+    r.select(0)
+    torch.cuda.synchronize()
+    assert torch.equal(r.idx, step_idx)
+
+
+def test_quantised_scores_tie_in_every_ranking():
+    """Few distinct score values: the rankings are decided by their tie rules (position, best rank)."""
+    def quant(k):
+        k.copy_(torch.sign(k) * (k.abs() > 0.8))   # keys in {-1, 0, 1}: scores collide heavily
+    for mode in (1, 2):
+        _with_keys(small(f"rankties{mode}", batch=2, seq_len=2000, budget=256, window=64), quant, rank_mode=mode)
 
 
 def test_strided_contiguous_cache_view():
