@@ -35,6 +35,9 @@ def parse():
                     help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
+    ap.add_argument("--rank-study", action="store_true",
+                    help="also compare the three readings of the global ranking and the per-head sets: overlap of rho "
+                         "and attention recall (Eq. 3) on the selection layer and on the last sparse layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-baseline", action="store_true")
     ap.add_argument("--no-per-head", action="store_true",
@@ -110,6 +113,37 @@ def per_head_comparison(r, w, sched, lens, steps, torch, cb, acc):
             "kernel_bytes": {"unified": b_uni, "per_head": b_ph},
             "per_head_GBs": round(b_ph / (kp_us * 1e-6) / 1e9, 1),
             "distinct_rows_per_group_over_list": round(distinct, 3), "gqa_group": g}
+
+
+def rank_study(inp, w, sched, torch, StepRunner):
+    """How much the readings of "globally ranked" differ on this workload: |rho ∩ rho_first| / |rho| and the
+    recall of Eq. 3 (mean and minimum over sequences and heads), on the selection layer's own q, K and on the
+    last sparse layer's (rho reused there); per-head sets (every head its own top-k) for comparison."""
+    sel = sched.index(1)
+    last = max(i for i, k in enumerate(sched) if k == 2)
+    names = {0: "first_occurrence", 1: "votes", 2: "max_score"}
+    res, base = {}, None
+
+    def stats(t):
+        return {"mean": round(float(t.mean()), 5), "min": round(float(t.min()), 5)}
+
+    for mode in (0, 1, 2):
+        r = StepRunner(inp, sched, rank_mode=mode)
+        r.select(sel)
+        torch.cuda.synchronize()
+        rho = [set(r.idx[b, : int(r.cnt[b])].tolist()) for b in range(w.batch)]
+        if base is None:
+            base = rho
+        same = sum(len(a & b) for a, b in zip(rho, base)) / sum(len(a) for a in rho)
+        res[names[mode]] = {"share_of_rho_in_first_occurrence_rho": round(same, 5),
+                            "recall_select_layer": stats(r.recall(sel)), "recall_last_sparse_layer": stats(r.recall(last))}
+        if mode == 0:
+            idx_head = r.make_idx_head()
+            r.select_per_head(sel, idx_head)
+            res["per_head_sets"] = {"recall_select_layer": stats(r.recall(sel, idx_head)),
+                                    "recall_last_sparse_layer": stats(r.recall(last, idx_head))}
+        del r
+    return res
 
 
 def cpu_baseline(inp, w, sched):
@@ -259,6 +293,8 @@ def main():
         out["speedup_vs_full_attention"] = round(full_s / step_s, 3)
     if not args.no_per_head and 2 in sched:
         out["per_head_comparison"] = per_head_comparison(r, w, sched, lens, max(3, args.steps // 2), torch, cb, acc)
+    if args.rank_study and 2 in sched:
+        out["rank_study"] = rank_study(inp, w, sched, torch, StepRunner)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, w, sched)
     print(json.dumps(out), flush=True)

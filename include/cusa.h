@@ -154,6 +154,17 @@ cusa_status cusa_sparse_attn_per_head(const cusa_params* params, const void* q, 
                                       const int32_t* idx_head, const int32_t* cnt, void* out,
                                       void* ws, size_t ws_bytes, void* stream);
 
+/* Attention recall of Eq. 3 for a given token set: recall[b][h] = (softmax mass of head h
+ * on the set) / (its mass on all L_b tokens) = sum_{t in set} exp(s_t) / sum_{t < L_b} exp(s_t)
+ * with s_t = sm_scale * q_h.k_t.  Two attention passes (over the set, over all tokens) keep
+ * their softmax denominators; a diagnostic, not a step of Alg. 1.
+ * idx, cnt      as in cusa_sparse_attn (idx_per_head = 0) or as in
+ *               cusa_sparse_attn_per_head (idx_per_head = 1).
+ * recall        device float [batch][n_q_heads]. */
+cusa_status cusa_attention_recall(const cusa_params* params, const void* q, const cusa_kv* kv,
+                                  const int32_t* idx, const int32_t* cnt, int32_t idx_per_head,
+                                  float* recall, void* ws, size_t ws_bytes, void* stream);
+
 /* FullAttention(q, C[:]) of Alg. 1 (Eq. 1 over all L_b tokens); also the
  * baseline the sparse path is compared with.  budget, window and topk_per_head
  * do not enter the result, but params is validated as a whole (so they must

@@ -18,11 +18,11 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
-                                             "rank_aggregate_kernel"};
+                                             "rank_aggregate_kernel", "recall_kernel"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -175,7 +175,7 @@ AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
 }
 
 struct WsLayout {
-    size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, total;
+    size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, lse, out_tmp, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -203,6 +203,8 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
         w.agg = off;       off += align256((size_t)(B * 2 * w.ldp) * 4);
         w.rho_rank = off;  off += align256((size_t)(B * (p->budget - p->window + 1)) * 4);
     }
+    w.lse = off;      off += align256((size_t)(B * H * 2) * 4);        // recall: denominators over the set and over all tokens
+    w.out_tmp = off;  off += align256((size_t)(B * H * D) * 2);        // recall: the attention outputs nobody reads
     w.total = off;
     return w;
 }
@@ -247,6 +249,7 @@ struct AttnArgs {
     float* pa;
     float* pm;
     uint16_t* out;
+    float* lse = nullptr;   // optional: log2 of the softmax denominators, [B][H]
     int n_splits, chunk;
     ScoreOut score;
 };
@@ -256,10 +259,10 @@ void launch_attn_partial(const AttnArgs& a) {
     const int kid = SPARSE ? KID_ATTN_SPARSE : SCORE ? KID_ATTN_SELECT : KID_ATTN_FULL;
     if (a.paged)
         launch(kid, attn_kernel<GQ, TI, SPARSE, true, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, 0, a.view);
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.view);
     else
         launch(kid, attn_kernel<GQ, TI, SPARSE, false, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.score.P, a.score.ldp, a.score.window, 0, a.view);
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.view);
 }
 
 // Sparse attention with one token list per query head: grid.y counts query heads.
@@ -267,10 +270,10 @@ template <int TI>
 void launch_attn_per_head(const AttnArgs& a, int H, int hshift) {
     if (a.paged)
         launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, true, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
-               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, nullptr, 0, 0, hshift, a.view);
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, a.view);
     else
         launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, false, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
-               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, nullptr, 0, 0, hshift, a.view);
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, a.view);
 }
 
 template <int GQ, bool SPARSE>
@@ -294,7 +297,7 @@ void launch_attn_ti(int ti, const AttnArgs& a) {
 template <bool SPARSE>
 cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv, const int32_t* idx,
                           const int32_t* cnt, int n_max, void* out, void* ws, const WsLayout& w, hipStream_t s,
-                          ScoreOut score = ScoreOut()) {
+                          ScoreOut score = ScoreOut(), float* lse = nullptr) {
     const int g = p->n_q_heads / p->n_kv_heads, BG = p->batch * p->n_kv_heads, H = p->n_q_heads;
     const AttnPlan pl = plan_attn(n_max, BG, g, score.P != nullptr);
     if (pl.n_splits > w.max_splits) return CUSA_ERR_WORKSPACE_TOO_SMALL;
@@ -311,6 +314,7 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     a.pa = ws_ptr<float>(ws, w.part_acc);
     a.pm = ws_ptr<float>(ws, w.part_ml);
     a.out = static_cast<uint16_t*>(out);
+    a.lse = lse;
     a.n_splits = pl.n_splits;
     a.chunk = pl.chunk;
     a.score = score;
@@ -323,14 +327,15 @@ cusa_status run_attention(const cusa_params* p, const void* q, const cusa_kv* kv
     if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
     if (pl.n_splits > 1) {
         launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, a.pa, a.pm, a.out, SPARSE ? cnt : kv->seq_lens,
-               SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H);
+               SPARSE ? p->budget : 0x7fffffff, pl.n_splits, pl.chunk, H, lse);
     }
     return launch_status();
 }
 
 // Sparse attention over idx_head [B][H][budget]: every query head is its own "group".
 cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cusa_kv* kv, const int32_t* idx_head,
-                                   const int32_t* cnt, void* out, void* ws, const WsLayout& w, hipStream_t s) {
+                                   const int32_t* cnt, void* out, void* ws, const WsLayout& w, hipStream_t s,
+                                   float* lse = nullptr) {
     const int H = p->n_q_heads, g = H / p->n_kv_heads;
     const int n_max = p->budget < kv->max_seq_len ? p->budget : kv->max_seq_len;
     const AttnPlan pl = plan_attn(n_max, p->batch * H, 1);
@@ -348,6 +353,7 @@ cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cu
     a.pa = ws_ptr<float>(ws, w.part_acc);
     a.pm = ws_ptr<float>(ws, w.part_ml);
     a.out = static_cast<uint16_t*>(out);
+    a.lse = lse;
     a.n_splits = pl.n_splits;
     a.chunk = pl.chunk;
     const int hshift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
@@ -356,7 +362,7 @@ cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cu
     if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
     if (pl.n_splits > 1)
         launch(KID_REDUCE, attn_reduce_kernel, dim3(H, p->batch), 256, 0, s, a.pa, a.pm, a.out, cnt, p->budget, pl.n_splits,
-               pl.chunk, H);
+               pl.chunk, H, lse);
     return launch_status();
 }
 
@@ -564,6 +570,30 @@ cusa_status cusa_sparse_attn_per_head(const cusa_params* params, const void* q, 
     const WsLayout w = make_layout(params, kv->max_seq_len);
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     return run_attention_per_head(params, q, kv, idx_head, cnt, out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_attention_recall(const cusa_params* params, const void* q, const cusa_kv* kv, const int32_t* idx,
+                                  const int32_t* cnt, int32_t idx_per_head, float* recall, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx || !cnt || !recall || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int n = params->batch * params->n_q_heads;
+    float* lse_set = ws_ptr<float>(ws, w.lse);
+    float* lse_all = lse_set + n;
+    void* out_tmp = ws_ptr<uint16_t>(ws, w.out_tmp);
+    const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
+    if (idx_per_head) st = run_attention_per_head(params, q, kv, idx, cnt, out_tmp, ws, w, s, lse_set);
+    else st = run_attention<true>(params, q, kv, idx, cnt, n_max, out_tmp, ws, w, s, ScoreOut(), lse_set);
+    if (st != CUSA_OK) return st;
+    st = run_attention<false>(params, q, kv, nullptr, nullptr, kv->max_seq_len, out_tmp, ws, w, s, ScoreOut(), lse_all);
+    if (st != CUSA_OK) return st;
+    launch(KID_RECALL, recall_kernel, (n + 255) / 256, 256, 0, s, lse_set, lse_all, recall, n);
+    return launch_status();
 }
 
 cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv, void* out, void* ws,

@@ -1046,6 +1046,9 @@ __device__ __forceinline__ void wave_lds_sync() {
 // as the k = 1 MFMA chain of score_kernel -- the pinned left-to-right binary32 sum -- instead of
 // the k = 4 bf16 MFMA, and the softmax uses those same values.
 //
+// lse (optional): log2 of each head's softmax denominator, M + log2(l) with scores scaled by
+// sm_scale * log2(e); written by whoever writes the head's output (this kernel or the reduce).
+//
 // PER_HEAD (sparse, GQ = 1): every query head attends its own token list idx[b][head][0 .. cnt[b])
 // -- the head-to-head selection the paper compares with (Sec. 3.2, the generalization figure) --
 // so a workgroup serves one query head, blockIdx.y counts query heads (G of them) and head y reads
@@ -1054,8 +1057,8 @@ template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
     const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
-    float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ P,
-    int64_t ldp, int window, int hshift, KvView kv) {
+    float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ lse,
+    float* __restrict__ P, int64_t ldp, int window, int hshift, KvView kv) {
     static_assert(!(SCORE && SPARSE), "scores are emitted by the pass over all tokens");
     static_assert(!PER_HEAD || (SPARSE && GQ == 1), "per-head token lists: one query head per workgroup");
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
@@ -1299,6 +1302,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         }
         if (n <= chunk) {                                // this workgroup saw the whole token list
             out[(head0 + h) * D + col] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
+            if (lse && col == 0) lse[head0 + h] = M + log2f(Ls);
         } else {
             const int64_t p = (head0 + h) * n_splits + split;
             part_acc[p * D + col] = A;
@@ -1319,7 +1323,8 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
                                                            const float* __restrict__ part_ml,
                                                            uint16_t* __restrict__ out,
                                                            const int32_t* __restrict__ n_tok, int n_clip,
-                                                           int stride_splits, int chunk, int H) {
+                                                           int stride_splits, int chunk, int H,
+                                                           float* __restrict__ lse) {
     __shared__ float red_a[8][D];
     __shared__ float red_m[8], red_l[8];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, c4 = tid & 31, sr = tid >> 5;
@@ -1393,7 +1398,17 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
             Ls = __builtin_fmaf(red_l[j], f, Ls);
         }
         out[((int64_t)b * H + h) * D + tid] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
+        if (lse && tid == 0) lse[(int64_t)b * H + h] = M + log2f(Ls);
     }
+}
+
+// Attention recall (Eq. 3): the share of a head's softmax mass that falls on its token set.  With
+// lse = log2 of the softmax denominator (scores scaled by sm_scale * log2 e) over the set and over
+// all tokens, the ratio of the two denominators is 2^(lse_set - lse_all).
+__global__ void recall_kernel(const float* __restrict__ lse_set, const float* __restrict__ lse_all,
+                              float* __restrict__ recall, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) recall[i] = exp2f(lse_set[i] - lse_all[i]);
 }
 
 }  // namespace cusa

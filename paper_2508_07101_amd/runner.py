@@ -65,6 +65,14 @@ class StepRunner:
         cb.sparse_attn_per_head(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], idx_head, self.cnt,
                                 self.outs[layer_pos], self.ws)
 
+    def recall(self, layer_pos: int, idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Eq. 3 on this layer's q and K for the current rho (idx None) or for per-head sets idx [B, H, budget]."""
+        w = self.inp.workload
+        out = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device=self.idx.device)
+        cb.attention_recall(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos],
+                            self.idx if idx is None else idx, self.cnt, out, self.ws, per_head=idx is not None)
+        return out
+
     def full(self, layer_pos: int):
         cb.full_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.ws)
 

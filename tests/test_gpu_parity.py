@@ -353,6 +353,39 @@ def test_quantised_scores_tie_in_every_ranking():
         _with_keys(small(f"rankties{mode}", batch=2, seq_len=2000, budget=256, window=64), quant, rank_mode=mode)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=32, batch=3, seq_len=1500, lengths=(1500, 200, 1033)),
+    dict(n_q_heads=64, batch=2, seq_len=6000, min_seq_len=5000, paged=True, budget=512, window=128),
+], ids=["ragged", "g8_paged_long"])
+def test_attention_recall_matches_the_oracle(kw):
+    """Eq. 3 for the unified set and for per-head sets, from the kernels' softmax denominators."""
+    base = dict(n_kv_heads=8, n_planted=6)
+    base.update(kw)
+    w = small("recall", **base)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.select(0)
+    rec = r.recall(0)
+    idx_head = r.make_idx_head()
+    r.select_per_head(0, idx_head)
+    rec_h = r.recall(0, idx_head)
+    torch.cuda.synchronize()
+    idx, cnt = r.idx.cpu().numpy(), r.cnt.cpu().numpy()
+    ih = idx_head.cpu().numpy()
+    g = w.n_q_heads // w.n_kv_heads
+    for b in range(w.batch):
+        q, K, _ = host_view(inp, 0, b)
+        want = oracle.recall(q, K, idx[b, : cnt[b]])
+        np.testing.assert_allclose(rec[b].cpu().numpy(), want, atol=1e-3, rtol=0)
+        want_h = np.array([oracle.recall(q[h:h + 1], K[h // g:h // g + 1], ih[b, h, : cnt[b]])[0]
+                           for h in range(w.n_q_heads)])
+        np.testing.assert_allclose(rec_h[b].cpu().numpy(), want_h, atol=1e-3, rtol=0)
+        if inp.seq_lens_host[b] <= w.budget:
+            np.testing.assert_allclose(want, 1.0)                       # the set is every token
+        else:
+            assert (want_h >= want - 1e-12).all()                      # a head's own top-k is its best set of that size
+
+
 def test_strided_contiguous_cache_view():
     """K/V given as [B, L, G, d] storage viewed as [B, G, L, d] (token stride G*d)."""
     w = small("strided", batch=2, seq_len=900)
