@@ -129,17 +129,23 @@ def unify(rho_head: np.ndarray, L: int, K: int, W: int, rank_mode: int = 0,
 
 
 def select(q: np.ndarray, K: np.ndarray, budget: int, window: int, topk_per_head: int = 0,
-           rank_mode: int = 0, return_all: bool = False):
-    """Token selection of Alg. 1 for one sequence: scores -> per-head top-k -> rho."""
+           rank_mode: int = 0, return_all: bool = False, n_sink: int = 0):
+    """Token selection of Alg. 1 for one sequence: scores -> per-head top-k -> rho.
+
+    n_sink (Sec. 4.1 reserves four tokens as attention sinks; reading: inside the budget): the
+    first n_sink positions are always in rho and are no candidates; the heads rank the positions
+    [n_sink, L-W) and the unified list keeps K - W - n_sink of them, so |rho| stays K."""
     L = K.shape[1]
     k = topk_per_head if topk_per_head > 0 else budget - window
+    assert 0 <= n_sink <= budget - window
     if L <= budget:
         rho = np.arange(L, dtype=np.int32)
         return (rho, None, None) if return_all else rho
     Lc = L - window
     P = scores(q, K, Lc)
-    rho_head = topk(P, k)
-    rho = unify(rho_head, L, budget, window, rank_mode, P)
+    rho_head = topk(P[:, n_sink:], k) + n_sink                       # ranked picks among [n_sink, Lc)
+    hist_and_recent = unify(rho_head, L, budget - n_sink, window, rank_mode, P)
+    rho = np.concatenate([np.arange(n_sink, dtype=np.int32), hist_and_recent]).astype(np.int32)
     return (rho, rho_head, P) if return_all else rho
 
 
@@ -165,7 +171,7 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, idx: Optional[np.ndar
     return (out, o64) if want_f64 else out
 
 
-def select_per_head(q: np.ndarray, K: np.ndarray, budget: int, window: int) -> np.ndarray:
+def select_per_head(q: np.ndarray, K: np.ndarray, budget: int, window: int, n_sink: int = 0) -> np.ndarray:
     """Head-to-head selection (the per-head variant CUSA is compared with, Sec. 3.2 and the
     generalization figure): head h keeps its own top-(K-W) candidates plus the last W positions.
     Returns rho_h[H, min(K, L)], every row ascending."""
@@ -173,9 +179,9 @@ def select_per_head(q: np.ndarray, K: np.ndarray, budget: int, window: int) -> n
     if L <= budget:
         return np.tile(np.arange(L, dtype=np.int32), (H, 1))
     Lc = L - window
-    picks = topk(scores(q, K, Lc), budget - window)                  # [H, K-W] ranked, distinct per row
-    recent = np.tile(np.arange(Lc, L, dtype=np.int32), (H, 1))
-    return np.sort(np.concatenate([picks, recent], axis=1), axis=1).astype(np.int32)
+    picks = topk(scores(q, K, Lc)[:, n_sink:], budget - window - n_sink) + n_sink   # ranked, distinct per row
+    fixed = np.concatenate([np.arange(n_sink, dtype=np.int32), np.arange(Lc, L, dtype=np.int32)])
+    return np.sort(np.concatenate([picks, np.tile(fixed, (H, 1))], axis=1), axis=1).astype(np.int32)
 
 
 def attention_per_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, idx_head: np.ndarray,
@@ -204,7 +210,7 @@ def recall(q: np.ndarray, K: np.ndarray, idx: np.ndarray, sm_scale: Optional[flo
 
 def decode_step(layer_kind: Sequence[int], q_layers, k_layers, v_layers, budget: int,
                 window: int, topk_per_head: int = 0, rank_mode: int = 0,
-                sm_scale: Optional[float] = None):
+                sm_scale: Optional[float] = None, n_sink: int = 0):
     """Attention part of Alg. 1 for ONE sequence over all layers.
 
     q_layers[i]: [H,d]; k_layers[i], v_layers[i]: [G,L,d] (bf16 bits).  A full
@@ -219,7 +225,7 @@ def decode_step(layer_kind: Sequence[int], q_layers, k_layers, v_layers, budget:
             outs.append(attention(q, K, V, None, sm_scale))
         elif kind == LAYER_SELECT:
             outs.append(attention(q, K, V, None, sm_scale))
-            rho = select(q, K, budget, window, topk_per_head, rank_mode)
+            rho = select(q, K, budget, window, topk_per_head, rank_mode, n_sink=n_sink)
         elif kind == LAYER_SPARSE:
             if rho is None:
                 raise ValueError("sparse layer before any selection layer (rho is empty)")

@@ -243,3 +243,43 @@ def test_per_head_selection_with_one_head_is_the_unified_selection():
     q, Kc, _ = rand_qkv(rng, 1, 1, 250)
     np.testing.assert_array_equal(oracle.select_per_head(q, Kc, 48, 12)[0], oracle.select(q, Kc, 48, 12))
     np.testing.assert_array_equal(oracle.select_per_head(q, Kc, 300, 12)[0], np.arange(250))   # budget covers L
+
+
+# ---------------------------------------------------------------- attention sinks (Sec. 4.1)
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_sinks_are_always_kept_and_never_ranked(mode):
+    rng = np.random.default_rng(81 + mode)
+    H, G, L, K, W, S = 8, 2, 300, 64, 16, 4
+    q, Kc, _ = rand_qkv(rng, H, G, L)
+    rho, rho_head, P = oracle.select(q, Kc, K, W, rank_mode=mode, return_all=True, n_sink=S)
+    assert len(rho) == K and (np.diff(rho) > 0).all()
+    assert rho[:S].tolist() == list(range(S)) and set(range(L - W, L)) <= set(rho)
+    assert rho_head.min() >= S and rho_head.max() < L - W              # sinks and window are no candidates
+    for h in range(H):                                                 # each head: its best among [S, L-W)
+        want = (np.argsort(-P[h, S:], kind="stable")[: rho_head.shape[1]] + S).tolist()
+        assert rho_head[h].tolist() == want
+    # the same problem with the sink keys cut out of the cache, shifted back: same picks
+    rho_cut = oracle.select(q, Kc[:, S:], K - S, W, topk_per_head=K - W, rank_mode=mode)   # same k per head
+    assert (rho_cut + S).tolist() == rho[S:].tolist()
+
+
+def test_sinks_zero_is_the_plain_selection_and_sinks_fill_the_history():
+    rng = np.random.default_rng(85)
+    q, Kc, _ = rand_qkv(rng, 4, 2, 200)
+    np.testing.assert_array_equal(oracle.select(q, Kc, 40, 10, n_sink=0), oracle.select(q, Kc, 40, 10))
+    rho = oracle.select(q, Kc, 40, 10, n_sink=30)                       # K - W - S = 0: sinks + window only
+    assert rho.tolist() == list(range(30)) + list(range(190, 200))
+    np.testing.assert_array_equal(oracle.select(q, Kc, 300, 10, n_sink=4), np.arange(200))   # budget covers L
+
+
+def test_per_head_selection_with_sinks():
+    rng = np.random.default_rng(86)
+    H, G, L, K, W, S = 4, 2, 260, 48, 12, 4
+    q, Kc, _ = rand_qkv(rng, H, G, L)
+    rho_h = oracle.select_per_head(q, Kc, K, W, n_sink=S)
+    P = oracle.scores(q, Kc, L - W)
+    for h in range(H):
+        want = sorted(list(range(S)) + (np.argsort(-P[h, S:], kind="stable")[: K - W - S] + S).tolist()
+                      + list(range(L - W, L)))
+        assert rho_h[h].tolist() == want
