@@ -63,8 +63,9 @@ typedef struct {
     int32_t head_dim;       /* d = 128                                                         */
     int32_t budget;         /* K: tokens attended by a sparse layer, window included           */
     int32_t window;         /* W = K*r most recent tokens always kept, 0 <= W <= K             */
-    int32_t topk_per_head;  /* k picks proposed per head; 0 means K-W; K-W <= k <= 8192        */
-    int32_t n_sink;         /* reserved, must be 0                                             */
+    int32_t topk_per_head;  /* k picks proposed per head; 0 means K-W; K-W-n_sink <= k <= 8192 */
+    int32_t n_sink;         /* attention sinks (Sec. 4.1 reserves four): the first n_sink       */
+                            /* positions are always in rho, inside the budget; 0 <= n_sink <= K-W */
     int32_t rank_mode;      /* cusa_rank_mode                                                  */
     float   sm_scale;       /* softmax scale of Eq. 1, normally 1/sqrt(d)                      */
 } cusa_params;
@@ -118,10 +119,11 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
  * Sec. 3.2 and 3.3).  For each sequence b with L = seq_lens[b]:
  *   L <= K : rho = {0 .. L-1}
  *   else   : P = q.K^T (unscaled, binary32, summed left to right over d) for
- *            tokens [0, L-W); every head ranks its min(k, L-W) best tokens by
- *            (score descending, position ascending); the ranked lists are
- *            unified per rank_mode and the first K-W distinct tokens kept;
- *            the last W positions are added.
+ *            tokens [0, L-W); every head ranks its min(k, L-W-n_sink) best tokens
+ *            of [n_sink, L-W) by (score descending, position ascending); the
+ *            ranked lists are unified per rank_mode and the first K-W-n_sink
+ *            distinct tokens kept; the n_sink first and the W last positions
+ *            are added.
  * q    device bf16 [batch][n_q_heads][128], this layer's query.
  * idx  device int32 [batch][budget]: rho ascending; entries >= cnt[b] unspecified.
  * cnt  device int32 [batch]: |rho| = min(K, L_b).

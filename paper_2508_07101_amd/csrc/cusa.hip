@@ -92,12 +92,12 @@ cusa_status check_params(const cusa_params* p, bool need_budget) {
     if (need_budget) {
         if (p->budget < 1 || p->window < 0 || p->window > p->budget) return CUSA_ERR_INVALID_ARG;
         if (p->topk_per_head < 0) return CUSA_ERR_INVALID_ARG;
-        if (p->n_sink != 0) return CUSA_ERR_UNSUPPORTED;
+        if (p->n_sink < 0 || p->n_sink > p->budget - p->window) return CUSA_ERR_INVALID_ARG;
         if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE && p->rank_mode != CUSA_RANK_VOTES &&
             p->rank_mode != CUSA_RANK_MAX_SCORE)
             return CUSA_ERR_INVALID_ARG;
         const int k = resolved_k(p);
-        if (k < p->budget - p->window) return CUSA_ERR_INVALID_ARG;
+        if (k < p->budget - p->window - p->n_sink) return CUSA_ERR_INVALID_ARG;
         if (k > 8192) return CUSA_ERR_UNSUPPORTED;
     }
     return CUSA_OK;
@@ -385,11 +385,11 @@ bool allow_dynamic_lds(const void* fn, size_t bytes) {
 
 template <int ITEMS, int MTOP>
 cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                          int32_t* rho_head, int H, int k, int budget, int window, int raw) {
+                          int32_t* rho_head, int H, int k, int budget, int window, int raw, int n_sink) {
     const size_t shmem = ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
     if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
         return CUSA_ERR_LAUNCH;
-    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
     return launch_status();
 }
 
@@ -397,24 +397,24 @@ cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp,
 // candidates kept for the lower bound.
 template <int ITEMS>
 cusa_status launch_topk(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                        int32_t* rho_head, int H, int k, int budget, int window, int raw) {
-    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
-    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
-    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
-    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw);
+                        int32_t* rho_head, int H, int k, int budget, int window, int raw, int n_sink) {
+    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
+    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
+    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
+    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
 }
 
 // Ranked top-k of every row of P: rows (b, h) of length L_b - W, output rank-major out[b][j][h].
 // raw: the rows hold uint32 keys instead of scores.
 cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                     int32_t* out, int k, int budget, int window, int raw) {
+                     int32_t* out, int k, int budget, int window, int raw, int n_sink) {
     const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
     const dim3 tg(H, B);
-    if (items <= 4) return launch_topk<4>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
-    if (items <= 8) return launch_topk<8>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
-    if (items <= 16) return launch_topk<16>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
-    if (items <= 32) return launch_topk<32>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
-    return launch_topk<0>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw);
+    if (items <= 4) return launch_topk<4>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
+    if (items <= 8) return launch_topk<8>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
+    if (items <= 16) return launch_topk<16>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
+    if (items <= 32) return launch_topk<32>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
+    return launch_topk<0>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
 }
 
 template <int GQ>
@@ -456,14 +456,14 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
             }
             if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         }
-        cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0);
+        cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0, p->n_sink);
         if (st != CUSA_OK) return st;
     }
     {
         // the union's bitmap over candidate positions lives in LDS
         const int lc_max = kv->max_seq_len > p->window ? kv->max_seq_len - p->window : 0;
         const size_t bitmap = ((((size_t)lc_max + 31) / 32) * 4 + 255) & ~(size_t)255;
-        const int n_hist = p->budget - p->window;
+        const int n_hist = p->budget - p->window - p->n_sink;
         if (!per_head && p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {
             // votes / max-score readings: one key per candidate position, the K-W best positions by key
             // (the same ranked top-k kernel, one row per sequence), then the ascending emission
@@ -471,28 +471,28 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
             if (n_hist > 0 && kv->max_seq_len > p->budget) {
                 uint32_t* agg = ws_ptr<uint32_t>(ws, w.agg);
                 launch(KID_RANK_AGG, rank_aggregate_kernel, B, SEL_THREADS, 0, s, rho_head, P, w.ldp, kv->seq_lens, agg, w.ldp,
-                       H, w.k, p->budget, p->window, p->rank_mode == CUSA_RANK_MAX_SCORE ? 1 : 0);
+                       H, w.k, p->budget, p->window, p->rank_mode == CUSA_RANK_MAX_SCORE ? 1 : 0, p->n_sink);
                 if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
                 const cusa_status st = run_topk(lc_max, B, 1, s, reinterpret_cast<const float*>(agg), 2 * w.ldp, kv->seq_lens,
-                                                rho_rank, n_hist, p->budget, p->window, 1);
+                                                rho_rank, n_hist, p->budget, p->window, 1, p->n_sink);
                 if (st != CUSA_OK) return st;
             }
             if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
                 return CUSA_ERR_LAUNCH;
             launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(1, B), SEL_THREADS, bitmap, s, rho_rank, kv->seq_lens, idx, cnt, 1,
-                   n_hist, p->budget, p->window);
+                   n_hist, p->budget, p->window, p->n_sink);
             return launch_status();
         }
         if (per_head) {
             if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
                 return CUSA_ERR_LAUNCH;
             launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(H, B), SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H,
-                   w.k, p->budget, p->window);
+                   w.k, p->budget, p->window, p->n_sink);
             return launch_status();
         }
         if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel), bitmap)) return CUSA_ERR_LAUNCH;
         launch(KID_UNION, union_kernel, B, SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H, w.k, p->budget,
-               p->window);
+               p->window, p->n_sink);
     }
     return launch_status();
 }

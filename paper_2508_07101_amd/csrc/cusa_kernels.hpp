@@ -419,7 +419,7 @@ template <int ITEMS, int MTOP>
 __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
-                                                            int budget, int window, int raw_keys) {
+                                                            int budget, int window, int raw_keys, int n_sink) {
     constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
     constexpr int CAP = topk_list_cap(ITEMS, MTOP);
     extern __shared__ uint64_t sort_buf[];            // NSORT composites (aliases the histogram), then CAP list entries
@@ -433,7 +433,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     const int L = seq_lens[b];
     if (L <= budget) return;
     const int Lc = L - window;
-    const int k_eff = k < Lc ? k : Lc;
+    // the first n_sink positions are kept in rho anyway and are no candidates (key 0, like the padding)
+    const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
     const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
 
     CUSA_TRACE_POINT(0);
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         for (int i = 0; i < ITEMS; ++i) {
             const int t = i * SEL_THREADS + threadIdx.x;
             const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
-            keys[i] = t < Lc ? kv_ : 0u;
+            keys[i] = (t < Lc && t >= n_sink) ? kv_ : 0u;
         }
     }
     auto scan = [&](auto f) {
@@ -462,7 +463,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
                 for (int u = 0; u < 32; ++u) {
                     const int t = t0 + u * SEL_THREADS + threadIdx.x;
                     const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
-                    kk[u] = t < Lc ? kv_ : 0u;
+                    kk[u] = (t < Lc && t >= n_sink) ? kv_ : 0u;
                 }
 #pragma unroll
                 for (int u = 0; u < 32; ++u) f(kk[u], t0 + u * SEL_THREADS + (int)threadIdx.x);
@@ -667,13 +668,39 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
 // What is left set is the answer; it is emitted in ascending position order, followed by the
 // window {L-W .. L-1}.
 
+// Adds the sink positions 0 .. n_sink-1 (never picked: they are no candidates) to the set in
+// `bits` and writes the set's positions in ascending order, at most `limit` of them.  Thread i
+// owns the words [i * wpt, i * wpt + wpt).  Returns n_sink.
+__device__ __forceinline__ int emit_sinks_and_set(uint32_t* bits, int n_words, int n_sink, int limit, int* scratch,
+                                                  int32_t* __restrict__ out) {
+    const int tid = threadIdx.x;
+    for (int t = tid; t < n_sink; t += SEL_THREADS) atomicOr(&bits[t >> 5], 1u << (t & 31));
+    if (n_sink > 0) __syncthreads();
+    const int wpt = (n_words + SEL_THREADS - 1) / SEL_THREADS;
+    const int w_lo = tid * wpt, w_hi = (w_lo + wpt < n_words) ? w_lo + wpt : n_words;
+    int mine = 0;
+    for (int i = w_lo; i < w_hi; ++i) mine += __popc(bits[i]);
+    int total;
+    int off = block_scan_excl(mine, scratch, &total);
+    for (int i = w_lo; i < w_hi; ++i) {
+        uint32_t word = bits[i];
+        while (word) {
+            const int bpos = __ffs(word) - 1;
+            if (off < limit) out[off] = i * 32 + bpos;
+            ++off;
+            word &= word - 1;
+        }
+    }
+    return n_sink;
+}
+
 constexpr int UNION_UNROLL = 8;
 constexpr int UNION_MAX_POSITIONS = 144 * 1024 * 8;   // candidate positions a 144 KB bitmap covers
 
 __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __restrict__ rho_head,
                                                              const int32_t* __restrict__ seq_lens,
                                                              int32_t* __restrict__ idx, int32_t* __restrict__ cnt,
-                                                             int H, int k, int budget, int window) {
+                                                             int H, int k, int budget, int window, int n_sink) {
     extern __shared__ uint32_t bits[];                // ceil(Lc / 32) words
     __shared__ int wave_cnt[2 * SEL_WAVES];
     __shared__ int scratch[SEL_WAVES + 1];
@@ -687,9 +714,9 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         return;
     }
     const int Lc = L - window;
-    const int k_eff = k < Lc ? k : Lc;
+    const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
     const int S = k_eff * H;
-    const int n_hist = budget - window;
+    const int n_hist = budget - window - n_sink;      // picks to keep; the sink positions come on top
     const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
     const int n_words = (Lc + 31) >> 5;
 
@@ -827,23 +854,7 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         __syncthreads();
     }
     CUSA_TRACE_POINT(3);
-
-    // ascending emission: thread i owns the words [i * wpt, i * wpt + wpt)
-    const int wpt = (n_words + SEL_THREADS - 1) / SEL_THREADS;
-    const int w_lo = tid * wpt, w_hi = (w_lo + wpt < n_words) ? w_lo + wpt : n_words;
-    int mine = 0;
-    for (int i = w_lo; i < w_hi; ++i) mine += __popc(bits[i]);
-    int total;
-    int off = block_scan_excl(mine, scratch, &total);
-    for (int i = w_lo; i < w_hi; ++i) {
-        uint32_t word = bits[i];
-        while (word) {
-            const int bpos = __ffs(word) - 1;
-            if (off < n_hist) out[off] = i * 32 + bpos;
-            ++off;
-            word &= word - 1;
-        }
-    }
+    n_take += emit_sinks_and_set(bits, n_words, n_sink, n_hist + n_sink, scratch, out);
     CUSA_TRACE_POINT(4);
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;
@@ -862,12 +873,13 @@ __global__ __launch_bounds__(SEL_THREADS) void rank_aggregate_kernel(const int32
                                                                       const float* __restrict__ P, int64_t ldp,
                                                                       const int32_t* __restrict__ seq_lens,
                                                                       uint32_t* __restrict__ agg, int64_t ld_agg, int H,
-                                                                      int k, int budget, int window, int by_score) {
+                                                                      int k, int budget, int window, int by_score,
+                                                                      int n_sink) {
     const int b = blockIdx.x, tid = threadIdx.x;
     const int L = seq_lens[b];
     if (L <= budget) return;
     const int Lc = L - window;
-    const int k_eff = k < Lc ? k : Lc;
+    const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
     const int S = k_eff * H;
     uint32_t* const key = agg + (int64_t)b * 2 * ld_agg;
     uint32_t* const best = key + ld_agg;
@@ -909,7 +921,7 @@ __global__ __launch_bounds__(SEL_THREADS) void per_head_rho_kernel(const int32_t
                                                                     const int32_t* __restrict__ seq_lens,
                                                                     int32_t* __restrict__ idx_head,
                                                                     int32_t* __restrict__ cnt, int H, int k,
-                                                                    int budget, int window) {
+                                                                    int budget, int window, int n_sink) {
     extern __shared__ uint32_t bits[];                // ceil(Lc / 32) words
     __shared__ int scratch[SEL_WAVES + 1];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
@@ -921,8 +933,8 @@ __global__ __launch_bounds__(SEL_THREADS) void per_head_rho_kernel(const int32_t
         return;
     }
     const int Lc = L - window;
-    const int k_eff = k < Lc ? k : Lc;
-    const int n_hist = min(budget - window, k_eff);   // = K - W: k >= K - W and Lc > K - W here
+    const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
+    const int n_hist = min(budget - window - n_sink, k_eff);   // = K - W - n_sink: k is at least that, and so is Lc - n_sink
     const int n_words = (Lc + 31) >> 5;
     for (int i = tid; i < n_words; i += SEL_THREADS) bits[i] = 0u;
     __syncthreads();
@@ -932,23 +944,9 @@ __global__ __launch_bounds__(SEL_THREADS) void per_head_rho_kernel(const int32_t
         if ((uint32_t)t < (uint32_t)Lc) atomicOr(&bits[t >> 5], 1u << (t & 31));
     }
     __syncthreads();
-    const int wpt = (n_words + SEL_THREADS - 1) / SEL_THREADS;
-    const int w_lo = tid * wpt, w_hi = (w_lo + wpt < n_words) ? w_lo + wpt : n_words;
-    int mine = 0;
-    for (int i = w_lo; i < w_hi; ++i) mine += __popc(bits[i]);
-    int total;
-    int off = block_scan_excl(mine, scratch, &total);
-    for (int i = w_lo; i < w_hi; ++i) {
-        uint32_t word = bits[i];
-        while (word) {
-            const int bpos = __ffs(word) - 1;
-            if (off < n_hist) out[off] = i * 32 + bpos;
-            ++off;
-            word &= word - 1;
-        }
-    }
-    for (int j = tid; j < window; j += SEL_THREADS) out[n_hist + j] = L - window + j;
-    if (tid == 0 && h == 0) cnt[b] = n_hist + window;
+    const int n_take = n_hist + emit_sinks_and_set(bits, n_words, n_sink, n_hist + n_sink, scratch, out);
+    for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
+    if (tid == 0 && h == 0) cnt[b] = n_take + window;
 }
 
 // ---------------------------------------------------------------- attention (split-K flash-decode)

@@ -14,7 +14,7 @@ from .workloads import Inputs
 def params_of(inp: Inputs, rank_mode: int = cb.RANK_FIRST_OCCURRENCE) -> cb.CusaParams:
     w = inp.workload
     return cb.make_params(w.batch, w.n_q_heads, w.n_kv_heads, w.budget, w.window, w.topk_per_head,
-                          head_dim=w.head_dim, rank_mode=rank_mode)
+                          head_dim=w.head_dim, rank_mode=rank_mode, n_sink=w.n_sink)
 
 
 def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:

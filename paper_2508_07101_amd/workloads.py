@@ -55,6 +55,7 @@ class Workload:
     seed: int = BASE_SEED
     same_layer_sparse: bool = False   # single-layer configs: sparse pass on the selection layer's KV
     lengths: tuple = ()               # explicit per-sequence lengths (tests); overrides the draw
+    n_sink: int = 0                   # first positions always kept in rho (attention sinks, Sec. 4.1)
 
     @property
     def k_eff(self) -> int:

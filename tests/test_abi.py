@@ -48,7 +48,8 @@ def test_workspace_bytes_grows_with_the_problem():
     (dict(window=4096), cb.ERR_INVALID_ARG),               # W > K
     (dict(topk_per_head=100), cb.ERR_INVALID_ARG),         # k < K - W
     (dict(topk_per_head=10000), cb.ERR_UNSUPPORTED),
-    (dict(n_sink=4), cb.ERR_UNSUPPORTED),
+    (dict(n_sink=-1), cb.ERR_INVALID_ARG),
+    (dict(n_sink=1537), cb.ERR_INVALID_ARG),               # more sinks than K - W
     (dict(rank_mode=7), cb.ERR_INVALID_ARG),
     (dict(sm_scale=0.0), cb.ERR_INVALID_ARG),
     (dict(batch=0), cb.ERR_INVALID_ARG),

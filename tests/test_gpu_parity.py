@@ -37,7 +37,8 @@ def check_select(inp, runner, layer_pos, seqs=None, check_scores=True, rank_mode
     for b in (range(w.batch) if seqs is None else seqs):
         q, K, _ = host_view(inp, layer_pos, b)
         L = inp.seq_lens_host[b]
-        rho, rho_head, P = oracle.select(q, K, w.budget, w.window, w.topk_per_head, rank_mode, return_all=True)
+        rho, rho_head, P = oracle.select(q, K, w.budget, w.window, w.topk_per_head, rank_mode, return_all=True,
+                                         n_sink=w.n_sink)
         if L > w.budget:
             Lc = L - w.window
             if check_scores:
@@ -279,13 +280,13 @@ def test_standalone_entry_points_match_the_oracle(H, paged, L):
     check_attention(inp, r, 1, LAYER_SPARSE, seqs)
 
 
-@pytest.mark.parametrize("H,paged,lengths", [(8, False, (1500, 900, 1211)), (16, True, (100, 1500, 257)),
-                                             (32, False, (1500, 256, 1033)), (64, True, (1400, 1500, 700)),
-                                             (32, True, (9000, 300, 7001))])
-def test_per_head_selection_and_attention_match_the_oracle(H, paged, lengths):
+@pytest.mark.parametrize("H,paged,lengths,sinks", [(8, False, (1500, 900, 1211), 0), (16, True, (100, 1500, 257), 0),
+                                                   (32, False, (1500, 256, 1033), 4), (64, True, (1400, 1500, 700), 0),
+                                                   (32, True, (9000, 300, 7001), 4)])
+def test_per_head_selection_and_attention_match_the_oracle(H, paged, lengths, sinks):
     """Head-to-head variant: every head its own top-(K-W) + window, and sparse attention over it."""
     w = small(f"perhead{H}", n_q_heads=H, n_kv_heads=8, batch=len(lengths), seq_len=max(lengths), lengths=lengths,
-              paged=paged, n_planted=5)
+              paged=paged, n_planted=5, n_sink=sinks)
     inp = wl.make_inputs(w, DEV)
     r = StepRunner(inp)
     _say(f"{w.name}: per-head select + sparse attention, lens {inp.seq_lens_host}")
@@ -297,7 +298,7 @@ def test_per_head_selection_and_attention_match_the_oracle(H, paged, lengths):
     out = bf16_bits(r.outs[1])
     for b in range(w.batch):
         q, K, _ = host_view(inp, 0, b)
-        rho_h = oracle.select_per_head(q, K, w.budget, w.window)
+        rho_h = oracle.select_per_head(q, K, w.budget, w.window, w.n_sink)
         assert got_cnt[b] == rho_h.shape[1] == min(w.budget, inp.seq_lens_host[b])
         assert (got_idx[b, :, : got_cnt[b]] == rho_h).all(), f"per-head sets differ, seq {b}"
         q, K, V = host_view(inp, 1, b)
@@ -384,6 +385,32 @@ def test_attention_recall_matches_the_oracle(kw):
             np.testing.assert_allclose(want, 1.0)                       # the set is every token
         else:
             assert (want_h >= want - 1e-12).all()                      # a head's own top-k is its best set of that size
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=32, batch=3, seq_len=1500, lengths=(1500, 200, 1033), n_sink=4),
+    dict(n_q_heads=64, batch=2, seq_len=2600, paged=True, lowrank=4, budget=512, window=128, n_sink=4),
+    dict(n_q_heads=16, batch=2, seq_len=5000, min_seq_len=4000, budget=256, window=64, n_sink=40),
+    dict(n_q_heads=16, batch=2, seq_len=700, budget=128, window=64, n_sink=64),
+], ids=["ragged", "correlated_paged", "many_sinks", "sinks_fill_the_history"])
+def test_attention_sinks_are_kept_and_not_ranked(mode, kw):
+    """Sec. 4.1 reserves four sink tokens: positions below n_sink are always in rho and no candidates."""
+    base = dict(n_kv_heads=8, n_planted=6)
+    base.update(kw)
+    w = small(f"sinks{mode}", **base)
+    inp = wl.make_inputs(w, DEV)
+    # make the sink keys attractive, so that leaving them out of the ranking matters
+    inp.layers[0].k[:, :, : w.n_sink, :] = inp.layers[0].k[:, :, : w.n_sink, :] * 4
+    r = StepRunner(inp, rank_mode=mode)
+    _say(f"{w.name}: {w.n_sink} sinks, rank mode {mode}, lens {inp.seq_lens_host}")
+    r.run()
+    check_select(inp, r, 0, rank_mode=mode)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+    torch.cuda.synchronize()
+    for b, L in enumerate(inp.seq_lens_host):
+        if L > w.budget:
+            assert r.idx[b, : w.n_sink].tolist() == list(range(w.n_sink))
 
 
 def test_strided_contiguous_cache_view():
