@@ -30,7 +30,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "loop"],
+                    help="c1..c5: one decode step at fixed lengths (c2 is the configuration the metric is quoted on); "
+                         "loop: consecutive decode steps, every sequence one token longer after each")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -220,6 +222,14 @@ def main():
     torch.cuda.synchronize()
 
     run_step = r.run
+    if w.grow_room > 0:
+        if args.graph or args.steps + args.warmup > w.grow_room:
+            print(f"workload {w.name}: at most {w.grow_room} steps (warm-up included), and no --graph", file=sys.stderr)
+            sys.exit(2)
+
+        def run_step():                           # one decode step, then the sequences are one token longer
+            r.run()
+            r.grow(1)
     if args.graph:
         r.run()                                   # warm the library before capture
         torch.cuda.synchronize()
@@ -282,7 +292,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads}q/{w.n_kv_heads}kv heads, "
                                f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
                                f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
-                   "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream"},
+                   "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream",
+                   "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed"},
         "step_algorithmic_bytes": sb["total"],
         "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
         "roofline": roofline,

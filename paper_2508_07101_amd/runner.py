@@ -19,7 +19,7 @@ def params_of(inp: Inputs, rank_mode: int = cb.RANK_FIRST_OCCURRENCE) -> cb.Cusa
 
 def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:
     lay = inp.layers[layer_pos]
-    return cb.KvCache(lay.k, lay.v, inp.seq_lens, max(inp.seq_lens_host), inp.block_table)
+    return cb.KvCache(lay.k, lay.v, inp.seq_lens, max(inp.seq_lens_host) + inp.workload.grow_room, inp.block_table)
 
 
 class StepRunner:
@@ -32,7 +32,7 @@ class StepRunner:
         assert len(self.schedule) == len(inp.layers)
         dev = inp.seq_lens.device
         self.params = params_of(inp, rank_mode)
-        self.max_len = max(inp.seq_lens_host)
+        self.max_len = max(inp.seq_lens_host) + w.grow_room   # capacity: the lengths may grow up to it
         self.kvs = [kv_of(inp, i) for i in range(len(inp.layers))]
         self.outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
                      for _ in inp.layers]
@@ -44,6 +44,12 @@ class StepRunner:
 
     def run(self):
         self.step.run()
+
+    def grow(self, n: int = 1):
+        """Every sequence gets n more tokens (already present in the drawn caches), as after n decode steps."""
+        assert max(self.inp.seq_lens_host) + n <= self.max_len, "no room left in the caches"
+        self.inp.seq_lens.add_(n)
+        self.inp.seq_lens_host[:] = [v + n for v in self.inp.seq_lens_host]
 
     # single entry points on one layer (by position in inp.layers)
     def select(self, layer_pos: int):

@@ -56,6 +56,7 @@ class Workload:
     same_layer_sparse: bool = False   # single-layer configs: sparse pass on the selection layer's KV
     lengths: tuple = ()               # explicit per-sequence lengths (tests); overrides the draw
     n_sink: int = 0                   # first positions always kept in rho (attention sinks, Sec. 4.1)
+    grow_room: int = 0                # cache capacity beyond the drawn lengths (decode loops: L grows by one per step)
 
     @property
     def k_eff(self) -> int:
@@ -77,6 +78,12 @@ WORKLOADS: Dict[str, Workload] = {
                    n_planted=256, seed=BASE_SEED + 4, same_layer_sparse=True),
     "c5": Workload("c5", 4, 64, 32, 8, 128, 32768, 2048, 512, 0, _sched(0, 3),
                    min_seq_len=8192, paged=True, seed=BASE_SEED + 5),
+    # Steady-state decode loop (not one of the quoted configurations): the c2 model shape with the
+    # paper's experimental settings of Sec. 4.1 -- two full layers, a selection layer, a re-selection
+    # layer at layer 12, four sink tokens -- and room for the sequence to grow by one token per step.
+    "loop": Workload("loop", 36, 1, 32, 8, 128, 32768, 2048, 512, 0,
+                     _sched(2, 9) + (LAYER_SELECT,) + (LAYER_SPARSE,) * 23,
+                     n_planted=64, seed=BASE_SEED + 6, n_sink=4, lengths=(32768 - 256,), grow_room=256),
 }
 
 
@@ -174,9 +181,10 @@ def make_layer(w: Workload, layer: int, seq_lens_host: List[int], device,
 def make_inputs(w: Workload, device="cpu", layers: Optional[List[int]] = None) -> Inputs:
     """Draw the whole workload (or only the listed layer numbers) on ``device``."""
     lens = draw_lengths(w)
+    assert max(lens) + w.grow_room <= w.seq_len, "the drawn caches hold seq_len tokens"
     inp = Inputs(w, torch.tensor(lens, dtype=torch.int32, device=device), lens)
     if w.paged:
-        pages = [(n + w.page_size - 1) // w.page_size for n in lens]
+        pages = [(n + w.grow_room + w.page_size - 1) // w.page_size for n in lens]
         inp.n_pages = int(sum(pages))
         perm = torch.randperm(inp.n_pages, generator=_gen("cpu", w.seed)).to(torch.int32)
         table = torch.zeros((w.batch, max(pages)), dtype=torch.int32)

@@ -413,6 +413,45 @@ def test_attention_sinks_are_kept_and_not_ranked(mode, kw):
             assert r.idx[b, : w.n_sink].tolist() == list(range(w.n_sink))
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_decode_loop_growing_sequences_with_reselection(paged):
+    """Consecutive decode steps: every sequence one token longer after each step, rho rebuilt by the
+    selection layer and again by a re-selection layer (Sec. 4.1), four sink tokens.  One sequence
+    crosses the budget (L = K: everything, L = K + 1: selection) on the way."""
+    sched = (LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SELECT, LAYER_SPARSE)
+    w = small("loop", n_layers=5, schedule=sched, batch=3, seq_len=1500, lengths=(1490, 700, 255), grow_room=4,
+              paged=paged, n_sink=4, n_planted=5)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    for step in range(4):
+        _say(f"loop step {step}: lens {inp.seq_lens_host}")
+        r.idx.fill_(-1)
+        r.run()
+        check_select(inp, r, 3)                        # rho of the re-selection layer is the one left in idx
+        check_attention(inp, r, 0, LAYER_FULL)
+        check_attention(inp, r, 3, LAYER_SELECT)
+        check_attention(inp, r, 4, LAYER_SPARSE)
+        if step < 3:
+            r.grow(1)
+    assert inp.seq_lens_host == [1493, 703, 258] and inp.seq_lens.tolist() == inp.seq_lens_host
+
+
+def test_decode_loop_first_selection_feeds_the_layers_before_the_reselection():
+    """Layer 2 must attend the rho of layer 1's selection, not the re-selection's."""
+    sched = (LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SELECT, LAYER_SPARSE)
+    w = small("resel", n_layers=5, schedule=sched, batch=2, seq_len=1400, n_planted=5)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.run()
+    torch.cuda.synchronize()
+    out = bf16_bits(r.outs[2])
+    for b in range(w.batch):
+        q, K, _ = host_view(inp, 1, b)
+        rho1 = oracle.select(q, K, w.budget, w.window, w.topk_per_head)
+        q, K, V = host_view(inp, 2, b)
+        assert_close_bf16(out[b], oracle.attention(q, K, V, rho1), f"layer 2 seq {b}")
+
+
 def test_strided_contiguous_cache_view():
     """K/V given as [B, L, G, d] storage viewed as [B, G, L, d] (token stride G*d)."""
     w = small("strided", batch=2, seq_len=900)
