@@ -450,6 +450,41 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
             keys[i] = (t < Lc && t >= n_sink) ? kv_ : 0u;
         }
     }
+    // Streamed rows (ITEMS == 0) are walked in batches of SB keys per thread covering the positions
+    // [t0, t0 + SB * 1024): key u of a thread is position t0 + ((u / 4) * 1024 + thread) * 4 + u % 4, so a
+    // thread fetches 16 bytes at a time and a wave 1 KB per load.  Rows start 256-byte aligned and are
+    // padded to a multiple of 64 entries (ldp), so a load that starts below ldp stays inside the row;
+    // the others are clamped and, like everything at or past Lc, masked (loads stay unconditional).
+    constexpr int SB = 16;
+    auto stream_pos = [&](int t0, int u) { return t0 + ((u >> 2) * SEL_THREADS + (int)threadIdx.x) * 4 + (u & 3); };
+    // The loads of the next batch are issued before the current one is worked on.
+    auto stream_issue = [&](f32x4 (&x)[SB / 4], int t0) {
+#pragma unroll
+        for (int v = 0; v < SB / 4; ++v) {
+            const int t = stream_pos(t0, 4 * v);
+            x[v] = *reinterpret_cast<const f32x4*>(row + (t < (int)ldp ? t : (int)ldp - 4));
+        }
+    };
+    auto stream_take = [&](const f32x4 (&x)[SB / 4], uint32_t (&kk)[SB], int t0) {
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int t = stream_pos(t0, u);
+            const uint32_t kv_ = key_of(x[u >> 2][u & 3]);
+            kk[u] = (t < Lc && t >= n_sink) ? kv_ : 0u;
+        }
+    };
+    // f(keys of the batch, first position of the batch) for every batch of a streamed row
+    auto stream_batches = [&](auto f) {
+        f32x4 x[SB / 4];
+        stream_issue(x, 0);
+        for (int t0 = 0; t0 < Lc; t0 += SB * SEL_THREADS) {
+            uint32_t kk[SB];
+            stream_take(x, kk, t0);
+            stream_issue(x, t0 + SB * SEL_THREADS);    // past the row's end: clamped loads, never used
+            __builtin_amdgcn_sched_barrier(0);
+            f(kk, t0);
+        }
+    };
     auto scan = [&](auto f) {
         if constexpr (ITEMS > 0) {
 #pragma unroll
@@ -457,17 +492,10 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
                 f(keys[i], i * SEL_THREADS + (int)threadIdx.x);
             }
         } else {
-            for (int t0 = 0; t0 < Lc; t0 += 32 * SEL_THREADS) {
-                uint32_t kk[32];
+            stream_batches([&](const uint32_t (&kk)[SB], int t0) {
 #pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int t = t0 + u * SEL_THREADS + threadIdx.x;
-                    const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
-                    kk[u] = (t < Lc && t >= n_sink) ? kv_ : 0u;
-                }
-#pragma unroll
-                for (int u = 0; u < 32; ++u) f(kk[u], t0 + u * SEL_THREADS + (int)threadIdx.x);
-            }
+                for (int u = 0; u < SB; ++u) f(kk[u], stream_pos(t0, u));
+            });
         }
     };
 
@@ -476,19 +504,30 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     //    exceed the k_eff-th largest of all candidates, so its top digit d0 bounds the answer's
     //    from below and the first histogram pass may skip every key under d0 -- most of them,
     //    which matters because LDS histogram atomics are what this kernel is bound by.
-    uint32_t top[MTOP];
+    //    A streamed row keeps the maxima of 8 disjoint groups of the thread's candidates instead
+    //    (one instruction per key): distinct candidates again, so the same argument holds, and
+    //    with 8192 group maxima the bound is about as tight.
+    constexpr int MG = ITEMS > 0 ? MTOP : 8;
+    uint32_t top[MG];
 #pragma unroll
-    for (int j = 0; j < MTOP; ++j) top[j] = 0u;
+    for (int j = 0; j < MG; ++j) top[j] = 0u;
     CUSA_TRACE_POINT(1);
-    scan([&](uint32_t key, int) {
-        uint32_t x = key;
+    if constexpr (ITEMS > 0) {
+        scan([&](uint32_t key, int) {
+            uint32_t x = key;
 #pragma unroll
-        for (int j = 0; j < MTOP; ++j) {
-            const uint32_t hi = top[j] > x ? top[j] : x;
-            x = top[j] > x ? x : top[j];
-            top[j] = hi;
-        }
-    });
+            for (int j = 0; j < MTOP; ++j) {
+                const uint32_t hi = top[j] > x ? top[j] : x;
+                x = top[j] > x ? x : top[j];
+                top[j] = hi;
+            }
+        });
+    } else {
+        stream_batches([&](const uint32_t (&kk)[SB], int) {
+#pragma unroll
+            for (int u = 0; u < SB; ++u) top[u % MG] = top[u % MG] > kk[u] ? top[u % MG] : kk[u];
+        });
+    }
     for (int i = threadIdx.x; i < 2048; i += SEL_THREADS) hist[i] = 0;
     if (threadIdx.x == 0) {
         st.prefix = 0;
@@ -497,7 +536,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     }
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < MTOP; ++j) atomicAdd(&hist[top[j] >> 21], 1);
+    for (int j = 0; j < MG; ++j) atomicAdd(&hist[top[j] >> 21], 1);
     __syncthreads();
     pick_digit<2048>(hist, scratch, &st, 21);
     const uint32_t d0 = st.prefix >> 21;
@@ -553,6 +592,34 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     }
     __syncthreads();
     int listable = 0;
+    bool listed = false;
+    if constexpr (ITEMS == 0) {
+        // one walk does both: each batch is counted into the histogram, the wave reserves list
+        // slots for the batch's candidates and writes them (in arbitrary order; what is selected
+        // from the list does not depend on it)
+        stream_batches([&](const uint32_t (&kk)[SB], int t0) {
+            int n_new = 0;
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const uint32_t dg = kk[u] >> 21;
+                if (dg >= d0) {
+                    atomicAdd(&hist[dg], 1);
+                    ++n_new;
+                }
+            }
+            int slot = wave_reserve(n_new, &n_list);
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                if ((kk[u] >> 21) >= d0) {
+                    if (slot < CAP) cand[slot] = ((uint64_t)kk[u] << 32) | (uint32_t)~(uint32_t)stream_pos(t0, u);
+                    ++slot;
+                }
+            }
+        });
+        __syncthreads();
+        pick_digit<2048>(hist, scratch, &st, 21);
+        listed = n_list <= CAP;
+    } else {
     scan([&](uint32_t key, int) {
         const uint32_t dg = key >> 21;
         if (dg >= d0) {
@@ -562,7 +629,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     });
     __syncthreads();
     pick_digit<2048>(hist, scratch, &st, 21);
-    bool listed = false;
     if constexpr (CAP > 0) {
         int slot = wave_reserve(listable, &n_list);
         __syncthreads();
@@ -573,6 +639,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
             });
             __syncthreads();
         }
+    }
     }
     if (listed) {
         const int n = n_list;
