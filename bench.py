@@ -99,8 +99,9 @@ def per_head_comparison(r, w, sched, lens, steps, torch, cb, acc):
     t_ph = time_steps(per_head, steps, 2, torch)
     cb.profile_reset()
     cb.profile_enable(True)
-    unified()
-    per_head()
+    for _ in range(steps):
+        unified()
+        per_head()
     torch.cuda.synchronize()
     prof = cb.profile_read()
     cb.profile_enable(False)
