@@ -529,3 +529,43 @@ def test_c5_full_size_layer_subset_sampled_sequences():
         row = idx[b]
         assert (np.diff(row) > 0).all() and row[0] >= 0
         assert (row[-w.window:] == np.arange(lens[b] - w.window, lens[b])).all()
+
+
+def test_c2_full_size_per_head_variant():
+    """Head-to-head sets and their sparse attention at c2's shape, in the launch configuration the bench times."""
+    w = wl.WORKLOADS["c2"]
+    inp = wl.make_inputs(w, DEV, layers=[2, 3])
+    r = StepRunner(inp, [LAYER_SELECT, LAYER_SPARSE])
+    idx_head = r.make_idx_head()
+    r.select_per_head(0, idx_head)
+    r.sparse_per_head(1, idx_head)
+    torch.cuda.synchronize()
+    q, K, _ = host_view(inp, 0, 0)
+    rho_h = oracle.select_per_head(q, K, w.budget, w.window)
+    assert int(r.cnt[0]) == w.budget and (idx_head[0].cpu().numpy() == rho_h).all()
+    q, K, V = host_view(inp, 1, 0)
+    assert_close_bf16(bf16_bits(r.outs[1])[0], oracle.attention_per_head(q, K, V, rho_h), "c2 per-head attention")
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_c3_full_size_other_rankings_sampled_sequences(mode):
+    """Votes / max-score rankings on c3's correlated heads at full size (two of the eight sequences checked)."""
+    w = wl.WORKLOADS["c3"]
+    inp = wl.make_inputs(w, DEV, layers=[2, 3])
+    r = StepRunner(inp, [LAYER_SELECT, LAYER_SPARSE], rank_mode=mode)
+    r.run()
+    check_select(inp, r, 0, seqs=[0, 5], rank_mode=mode)
+    check_attention(inp, r, 1, LAYER_SPARSE, seqs=[5])
+
+
+def test_loop_workload_full_size_two_steps():
+    """The decode-loop workload's shape (re-selection layer, sinks), two consecutive steps on a layer subset."""
+    w = wl.scaled(wl.WORKLOADS["loop"], n_layers=5,
+                  schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SELECT, LAYER_SPARSE))
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    for step in range(2):
+        r.run()
+        check_select(inp, r, 3)
+        check_attention(inp, r, 4, LAYER_SPARSE)
+        r.grow(1)
