@@ -1068,6 +1068,8 @@ __host__ __device__ inline int attn_active_splits(int n, int chunk) {
 }
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // V_PERMLANE32_SWAP / V_PERMLANE16_SWAP exchange halves (rows 2,3 of a with rows 0,1 of b) or
 // odd/even 16-lane rows (rows 1,3 of a with rows 0,2 of b) of two registers.  Adding the two
@@ -1137,9 +1139,15 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
-    // A wave's softmax numerators, by token, take the place of its K rows once those are scored.
-    static_assert(TILE * 256 >= TILE * SETS * 16, "the numerators must fit the K tile buffer");
+    // A wave's softmax numerators take the place of its K rows once those are scored.  Groups of
+    // up to 4 heads keep them in binary32, by token.  A group of 8 is bound by the P.V products on
+    // the VALU and halves them with bf16 pair products (PAIRS): the numerators are stored as bf16,
+    // [pair of row loads j][row group r][head][member], so that the two tokens a lane multiplies
+    // together (rows 2j and 2j+1 of group r) sit in one 32-bit word per head.
+    constexpr bool PAIRS = GQ >= 8;
+    static_assert(TI % 2 == 0 && TILE * 256 >= TILE * SETS * 16, "the numerators must fit the K tile buffer");
     f32x4(*const pbuf)[SETS] = reinterpret_cast<f32x4(*)[SETS]>(ktile);
+    __bf16* const pbuf16 = reinterpret_cast<__bf16*>(ktile);
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[ATTN_WAVES][SETS * 4 * QSB];   // a private copy of q per wave
 
     CUSA_TRACE_POINT(0);
@@ -1192,6 +1200,8 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // heads of each set.  Lane t scores token t % TILE of the tile.
     const int tl = lane % TILE;
     const bool owner = lane < TILE;                   // lanes beyond TILE repeat a token; they add nothing to l
+    // token tl is row (tl / 4) of row group (tl % 4): where its numerators go
+    const int pair_slot = ((tl >> 3) * 4 + (tl & 3)), pair_member = (tl >> 2) & 1;
     float m[GQ], l[GQ], acc[GQ][8];
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
@@ -1289,28 +1299,65 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             const float m_new = fmaxf(m[h], mt);      // finite: token t0 of this tile is valid
             corr[h] = exp2f(m[h] - m_new);
             m[h] = m_new;
-            const float pz = exp2f(z - m_new);
+            float pz = exp2f(z - m_new);
+            if constexpr (PAIRS) {
+                // the weight enters numerator and denominator as the same bf16 value
+                const __bf16 pb = (__bf16)pz;
+                pbuf16[(pair_slot * GQ + h) * 2 + pair_member] = pb;
+                pz = (float)pb;
+            }
             l[h] = l[h] * corr[h] + (owner ? pz : 0.0f);
             sc[h >> 2][h & 3] = pz;
         }
+        if constexpr (!PAIRS) {
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) pbuf[tl][s] = sc[s];
+            for (int s = 0; s < SETS; ++s) pbuf[tl][s] = sc[s];
+        }
 #pragma unroll
         for (int h = 0; h < GQ; ++h)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[h][e] *= corr[h];
         wave_lds_sync();
+        if constexpr (!PAIRS) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) {
-            float vf[8];
-            unpack8(make_uint4(vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w), vf);
-            f32x4 pv[SETS];
+            for (int i = 0; i < TI; ++i) {
+                float vf[8];
+                unpack8(make_uint4(vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w), vf);
+                f32x4 pv[SETS];
 #pragma unroll
-            for (int s = 0; s < SETS; ++s) pv[s] = pbuf[i * 4 + r][s];
+                for (int s = 0; s < SETS; ++s) pv[s] = pbuf[i * 4 + r][s];
 #pragma unroll
-            for (int h = 0; h < GQ; ++h)
+                for (int h = 0; h < GQ; ++h)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pv[h >> 2][h & 3], vf[e], acc[h][e]);
+                    for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pv[h >> 2][h & 3], vf[e], acc[h][e]);
+            }
+        } else {
+            // P.V two tokens at a time: the rows 2j and 2j+1 of a lane (tokens 8j + r and 8j + 4 + r) are
+            // interleaved column by column into bf16 pairs, the two tokens' weights of a head arrive as one
+            // bf16 pair, and V_DOT2C_F32_BF16 adds both products to the binary32 accumulator.
+#pragma unroll
+            for (int j = 0; j < TI / 2; ++j) {
+                static_assert(!PAIRS || GQ % 4 == 0, "four heads' pairs are read at a time");
+                bf16x2 vp[8];
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    vp[2 * w2] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], 0x05040100u));
+                    vp[2 * w2 + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], 0x07060302u));
+                }
+                bf16x2 pp[GQ];
+                // same element type as the stores above: the compiler may otherwise take the two for unrelated
+                const bf16x8* const src = reinterpret_cast<const bf16x8*>(pbuf16 + (j * 4 + r) * GQ * 2);
+#pragma unroll
+                for (int q4 = 0; q4 < GQ / 4; ++q4) {
+                    const bf16x8 t8 = src[q4];             // four heads' pairs, one 16-byte read
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) pp[q4 * 4 + h] = bf16x2{t8[2 * h], t8[2 * h + 1]};
+                }
+#pragma unroll
+                for (int h = 0; h < GQ; ++h)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_amdgcn_fdot2_f32_bf16(vp[e], pp[h], acc[h][e], false);
+            }
         }
         wave_lds_sync();                              // the tile buffers are rewritten next iteration
     }
