@@ -772,6 +772,7 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     __shared__ int wave_cnt[2 * SEL_WAVES];
     __shared__ int scratch[SEL_WAVES + 1];
     __shared__ int picks[SEL_THREADS];                // the picks of the crossing 1024-slot range, by slot
+    __shared__ uint32_t idle[64];                     // where lanes with nothing to add send their atomic
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int L = seq_lens[b];
     int32_t* __restrict__ out = idx + (int64_t)b * budget;
@@ -834,11 +835,12 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         for (int u = 0; u < UNION_UNROLL; ++u) {
             // Neighbouring slots are neighbouring heads at one rank and often name the same token;
             // a lane whose left neighbour in its 16-lane row has the same pick leaves the atomic to it
-            // (same-address LDS atomics of one instruction are carried out one after the other).
+            // (same-address LDS atomics of one instruction are carried out one after the other; for
+            // the same reason the lanes that stay out add zero to a word of their own, not to a shared one).
             const int left = __builtin_amdgcn_update_dpp(-2, tok[u], 0x111, 0xF, 0xF, false);   // row_shr:1; -2 into lane 0 of a row
             const bool lead = tok[u] >= 0 && tok[u] != left;
             const uint32_t bit = 1u << (tok[u] & 31);
-            const uint32_t old = atomicOr(&bits[lead ? tok[u] >> 5 : 0], lead ? bit : 0u);
+            const uint32_t old = atomicOr(lead ? &bits[tok[u] >> 5] : &idle[lane], lead ? bit : 0u);
             const bool wn = lead && !(old & bit);
             if (wn) won |= 1u << u;
             wave_added += __popcll(__ballot(wn));
