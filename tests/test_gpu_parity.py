@@ -120,6 +120,11 @@ def test_four_layer_schedule_full_full_select_sparse():
     (1000, 128, 0, 0),      # no window
     (1000, 128, 128, 0),    # window only
     (1000, 64, 16, 1024),   # k far above K - W
+    (1777, 1000, 250, 0),   # sizes that are multiples of nothing
+    (4099, 333, 77, 401),
+    (777, 37, 5, 33),
+    (500, 1, 0, 0),         # budget of one token: the single best-ranked pick
+    (500, 1, 1, 0),         # budget of one token: the current token
 ])
 def test_edge_lengths_and_budgets(L, K, W, k):
     w = small(f"edge{L}_{K}_{W}_{k}", batch=2, seq_len=L, budget=K, window=W, topk_per_head=k)
