@@ -1224,11 +1224,12 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             const int pos = SPARSE ? min(max(pos_next[i], 0), L - 1) : min(t0 + i * 4 + r, end - 1);
             off[i] = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
         }
+        // K rows first: they are needed first (parked in LDS and scored), and loads return in
+        // order, so the scores are under way while the V rows are still arriving.
 #pragma unroll
-        for (int i = 0; i < TI; ++i) {
-            kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
-            vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
-        }
+        for (int i = 0; i < TI; ++i) kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
+#pragma unroll
+        for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
         if (SPARSE) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
