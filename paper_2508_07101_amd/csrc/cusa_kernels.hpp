@@ -1213,28 +1213,47 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
     }
 
-    for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
-        // Rows past the end of the run read some token of the sequence (a valid row) so that all
-        // loads are unconditional and issue back to back; their scores are masked below.
-        u32x4 kreg[TI], vreg[TI];
-        int64_t off[TI];
+    // Rows past the end of the run read some token of the sequence (a valid row) so that all
+    // loads are unconditional and issue back to back; their scores are masked below.
+    // The narrow variants (4 row loads per lane) have registers to spare and request the next
+    // tile's K rows as soon as this tile's are parked in LDS, i.e. before this tile's arithmetic.
+    constexpr bool PREFETCH = TI == 4 && !SCORE;
+    u32x4 kreg[TI], vreg[TI];
+    int64_t off[TI];
+    auto tile_offsets = [&](int t_) {
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
             // an index outside the sequence is a caller error; never fault on it
-            const int pos = SPARSE ? min(max(pos_next[i], 0), L - 1) : min(t0 + i * 4 + r, end - 1);
+            const int pos = SPARSE ? min(max(pos_next[i], 0), L - 1) : min(t_ + i * 4 + r, end - 1);
             off[i] = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
         }
-        // K rows first: they are needed first (parked in LDS and scored), and loads return in
-        // order, so the scores are under way while the V rows are still arriving.
+    };
+    auto request_k = [&]() {
 #pragma unroll
         for (int i = 0; i < TI; ++i) kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
-#pragma unroll
-        for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+    };
+    auto request_next_idx = [&](int t_) {              // the token indices of the tile that starts at t_
         if (SPARSE) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(t0 + WG_TILE + i * 4 + r, budget - 1)];
+            for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(t_ + i * 4 + r, budget - 1)];
         }
+    };
+    if (PREFETCH && begin + wave * TILE < end) {
+        tile_offsets(begin + wave * TILE);
+        request_k();
+        request_next_idx(begin + wave * TILE + WG_TILE);
+    }
+    for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
+        if constexpr (!PREFETCH) {
+            tile_offsets(t0);
+            // K rows first: they are needed first (parked in LDS and scored), and loads return in
+            // order, so the scores are under way while the V rows are still arriving.
+            request_k();
+        }
+#pragma unroll
+        for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+        if constexpr (!PREFETCH) request_next_idx(t0 + WG_TILE);
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         if (!q_parked) {
 #pragma unroll
@@ -1247,6 +1266,12 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             ktile[row * 16 + (c ^ (row & 7))] = kreg[i];
         }
         wave_lds_sync();
+        if (PREFETCH && t0 + WG_TILE < end) {
+            tile_offsets(t0 + WG_TILE);
+            request_k();
+            request_next_idx(t0 + 2 * WG_TILE);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         f32x4 sc[SETS];
 #pragma unroll
