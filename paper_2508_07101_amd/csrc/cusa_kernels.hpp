@@ -1215,9 +1215,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
 
     // Rows past the end of the run read some token of the sequence (a valid row) so that all
     // loads are unconditional and issue back to back; their scores are masked below.
-    // The narrow variants (4 row loads per lane) have registers to spare and request the next
-    // tile's K rows as soon as this tile's are parked in LDS, i.e. before this tile's arithmetic.
-    constexpr bool PREFETCH = TI == 4 && !SCORE;
+    // The next tile's K rows are requested as soon as this tile's are parked in LDS, i.e. before
+    // this tile's arithmetic (not in the scoring variant, whose 64-token tiles leave no registers).
+    constexpr bool PREFETCH = !SCORE;
     u32x4 kreg[TI], vreg[TI];
     int64_t off[TI];
     auto tile_offsets = [&](int t_) {
