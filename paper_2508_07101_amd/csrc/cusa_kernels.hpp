@@ -1150,7 +1150,12 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     static_assert(TI % 2 == 0 && TILE * 256 >= TILE * SETS * 16, "the numerators must fit the K tile buffer");
     f32x4(*const pbuf)[SETS] = reinterpret_cast<f32x4(*)[SETS]>(ktile);
     __bf16* const pbuf16 = reinterpret_cast<__bf16*>(ktile);
-    __shared__ __attribute__((aligned(16))) uint16_t qlds_all[ATTN_WAVES][SETS * 4 * QSB];   // a private copy of q per wave
+    // q in LDS: a private bf16 copy per wave, or -- in the scoring variant, whose product chain takes
+    // binary32 operands -- one binary32 copy for the workgroup (every wave writes all of it with the
+    // same values, so a wave depends on its own writes only and no workgroup barrier is needed).
+    constexpr int QSF = 132;                          // padded head stride of the binary32 copy (floats)
+    __shared__ __attribute__((aligned(16))) uint16_t qlds_all[SCORE ? 1 : ATTN_WAVES][SCORE ? 8 : SETS * 4 * QSB];
+    __shared__ __attribute__((aligned(16))) float qf32[SCORE ? SETS * 4 * QSF : 4];
 
     CUSA_TRACE_POINT(0);
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
@@ -1175,7 +1180,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // Every wave keeps its own bf16 copy of q in LDS (no workgroup barrier on the way in): lane l
     // fetches 16 bytes of head l / 16 per set now and parks them once the first tile's loads are
     // under way.  Heads beyond GQ score zero.
-    uint16_t* const qlds = qlds_all[wave];
+    uint16_t* const qlds = qlds_all[SCORE ? 0 : wave];
     u32x4 qv[SETS];
 #pragma unroll
     for (int s = 0; s < SETS; ++s) {
@@ -1257,7 +1262,17 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         if (!q_parked) {
 #pragma unroll
-            for (int s = 0; s < SETS; ++s) *reinterpret_cast<u32x4*>(&qlds[(s * 4 + r) * QSB + c * 8]) = qv[s];
+            for (int s = 0; s < SETS; ++s) {
+                if constexpr (SCORE) {
+                    float qf[8];
+                    unpack8(make_uint4(qv[s].x, qv[s].y, qv[s].z, qv[s].w), qf);
+                    float* const dst = &qf32[(s * 4 + r) * QSF + c * 8];
+                    *reinterpret_cast<f32x4*>(dst) = f32x4{qf[0], qf[1], qf[2], qf[3]};
+                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{qf[4], qf[5], qf[6], qf[7]};
+                } else {
+                    *reinterpret_cast<u32x4*>(&qlds[(s * 4 + r) * QSB + c * 8]) = qv[s];
+                }
+            }
             q_parked = true;
         }
 #pragma unroll
@@ -1285,8 +1300,13 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
                 float qf[SETS][8];
 #pragma unroll
                 for (int s = 0; s < SETS; ++s) {
-                    const u32x4 qw = *reinterpret_cast<const u32x4*>(&qlds[(s * 4 + (lane & 3)) * QSB + cc * 8]);
-                    unpack8(make_uint4(qw.x, qw.y, qw.z, qw.w), qf[s]);
+                    const float* const src = &qf32[(s * 4 + (lane & 3)) * QSF + cc * 8];
+                    const f32x4 qa = *reinterpret_cast<const f32x4*>(src), qb = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        qf[s][e] = qa[e];
+                        qf[s][4 + e] = qb[e];
+                    }
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
