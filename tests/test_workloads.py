@@ -73,3 +73,32 @@ def test_lowrank_component_correlates_heads():
     c = np.corrcoef(P)
     off = c[~np.eye(8, dtype=bool)]
     assert off.mean() > 0.2                                           # independent heads would give ~0
+
+
+def test_loop_workload_has_the_papers_settings_and_room_to_grow():
+    w = wl.WORKLOADS["loop"]
+    assert w.n_layers == 36 and len(w.schedule) == 36 and w.n_sink == 4
+    assert [i for i, k in enumerate(w.schedule) if k == 1] == [2, 12]     # selection layer and re-selection layer
+    assert w.schedule[:2] == (0, 0) and w.window * 4 == w.budget          # two full layers first; r = 0.25
+    assert wl.draw_lengths(w)[0] + w.grow_room <= w.seq_len
+
+
+def test_grow_room_reserves_pages_and_cache_rows():
+    w = _tiny(paged=True, lengths=(100, 17, 96), grow_room=40)
+    inp = wl.make_inputs(w, "cpu")
+    pages = [(n + 40 + 15) // 16 for n in w.lengths]
+    assert inp.n_pages == sum(pages) and inp.block_table.shape[1] == max(pages)
+    used = np.concatenate([inp.block_table[b, :n].numpy() for b, n in enumerate(pages)])
+    assert sorted(used.tolist()) == list(range(sum(pages)))          # the reserved pages are distinct pool pages too
+    c = wl.make_inputs(_tiny(lengths=(100, 17, 96), grow_room=40), "cpu")
+    assert c.layers[0].k.shape[2] >= 140                             # contiguous caches hold the grown length
+
+
+def test_decode_step_oracle_passes_the_sinks_on():
+    rng = np.random.default_rng(3)
+    from helpers import rand_qkv
+    q, K, V = rand_qkv(rng, 4, 2, 150)
+    outs, rho = oracle.decode_step([1, 2], [q, q], [K, K], [V, V], budget=32, window=8, n_sink=4)
+    np.testing.assert_array_equal(rho, oracle.select(q, K, 32, 8, n_sink=4))
+    np.testing.assert_array_equal(outs[1], oracle.attention(q, K, V, rho))
+    assert rho[:4].tolist() == [0, 1, 2, 3]
