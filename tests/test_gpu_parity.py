@@ -9,6 +9,7 @@ import torch
 
 import oracle
 from helpers import assert_close_bf16, host_view
+from paper_2508_07101_amd import binding as cb
 from paper_2508_07101_amd import workloads as wl
 from paper_2508_07101_amd.runner import StepRunner
 from paper_2508_07101_amd.workloads import LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, bf16_bits
@@ -574,3 +575,32 @@ def test_loop_workload_full_size_two_steps():
         check_select(inp, r, 3)
         check_attention(inp, r, 4, LAYER_SPARSE)
         r.grow(1)
+
+
+def test_longest_supported_selection():
+    """The longest sequence the selection accepts (its bitmap over candidate positions fills the LDS it may
+    use): 1 179 648 candidates plus the window, one sequence, eight heads."""
+    W = 64
+    L = 144 * 1024 * 8 + W
+    w = small("longest", n_q_heads=8, n_kv_heads=8, batch=1, seq_len=L, budget=256, window=W, n_planted=8)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    _say(f"longest: L = {L}")
+    r.run()
+    check_select(inp, r, 0)
+    check_attention(inp, r, 1, LAYER_SPARSE)
+    # the per-head emission and the votes ranking use the same bitmap at the same size
+    idx_head = r.make_idx_head()
+    r.select_per_head(0, idx_head)
+    torch.cuda.synchronize()
+    q, K, _ = host_view(inp, 0, 0)
+    assert (idx_head[0].cpu().numpy() == oracle.select_per_head(q, K, w.budget, w.window)).all()
+    r1 = StepRunner(inp, rank_mode=1)
+    r1.select(0)
+    check_select(inp, r1, 0, rank_mode=1, check_scores=False)
+    # one token more is refused on the host, before anything is launched
+    kv = r.kvs[0]
+    kv.max_seq_len += 1
+    with pytest.raises(cb.CusaError) as e:
+        cb.select(r.params, inp.layers[0].q, kv, r.idx, r.cnt, r.ws)
+    assert e.value.status in (cb.ERR_UNSUPPORTED, cb.ERR_WORKSPACE_TOO_SMALL)
