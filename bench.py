@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--rank-study", action="store_true",
                     help="also compare the three readings of the global ranking and the per-head sets: overlap of rho "
                          "and attention recall (Eq. 3) on the selection layer and on the last sparse layer")
+    ap.add_argument("--head-overlap", type=float, default=None, metavar="S",
+                    help="redraw the workload with a rank-8 component of scale S shared by all heads of a sequence "
+                         "(0 = independent heads, 4 = nearly identical picks): sets how much the heads' top-k sets overlap")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-baseline", action="store_true")
     ap.add_argument("--no-per-head", action="store_true",
@@ -216,6 +219,8 @@ def main():
     from paper_2508_07101_amd.runner import StepRunner
 
     w = wl.WORKLOADS[args.workload]
+    if args.head_overlap is not None:
+        w = wl.scaled(w, lowrank=8, lowrank_scale=args.head_overlap, n_planted=0)
     inp = wl.make_inputs(w, "cuda:0")
     sched = list(w.schedule)
     lens = inp.seq_lens_host
@@ -294,7 +299,8 @@ def main():
                                f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
                                f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
                    "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream",
-                   "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed"},
+                   "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed",
+                   **({"head_overlap": args.head_overlap} if args.head_overlap is not None else {})},
         "step_algorithmic_bytes": sb["total"],
         "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
         "roofline": roofline,
