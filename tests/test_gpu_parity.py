@@ -604,3 +604,48 @@ def test_longest_supported_selection():
     with pytest.raises(cb.CusaError) as e:
         cb.select(r.params, inp.layers[0].q, kv, r.idx, r.cnt, r.ws)
     assert e.value.status in (cb.ERR_UNSUPPORTED, cb.ERR_WORKSPACE_TOO_SMALL)
+
+
+def test_random_small_configurations():
+    """Forty seeded draws of the whole parameter space at small sizes: group size, batch, ragged lengths on
+    both sides of the budget, budgets and windows that are multiples of nothing, k above K - W, sinks, the
+    three rankings, both cache layouts."""
+    rng = np.random.default_rng(20250807)
+    for case in range(40):
+        g = int(rng.choice([1, 2, 4, 8]))
+        G = int(rng.choice([1, 2, 8]))
+        B = int(rng.integers(1, 5))
+        K = int(rng.integers(2, 700))
+        W = int(rng.integers(0, K + 1))
+        sinks = int(rng.integers(0, min(6, K - W) + 1))
+        k = 0 if rng.random() < 0.5 else int(rng.integers(max(K - W - sinks, 1), K - W + 400))
+        Lmax = int(rng.integers(K + 2, 3200))
+        lengths = tuple(int(v) for v in rng.integers(1, Lmax + 1, size=B))
+        lengths = (Lmax,) + lengths[1:]
+        mode = int(rng.integers(0, 3))
+        paged = bool(rng.random() < 0.5)
+        w = small(f"rand{case}", n_q_heads=G * g, n_kv_heads=G, batch=B, seq_len=Lmax, lengths=lengths, budget=K,
+                  window=W, topk_per_head=k, n_sink=sinks, paged=paged, n_planted=int(rng.integers(0, 4)),
+                  lowrank=int(rng.choice([0, 4])), seed=1000 + case)
+        _say(f"random case {case}: g={g} G={G} lens={lengths} K={K} W={W} k={k} sinks={sinks} mode={mode} paged={paged}")
+        inp = wl.make_inputs(w, DEV)
+        r = StepRunner(inp, rank_mode=mode)
+        r.run()
+        check_select(inp, r, 0, rank_mode=mode)
+        check_attention(inp, r, 0, LAYER_SELECT)
+        check_attention(inp, r, 1, LAYER_SPARSE)
+        if case % 4 == 0:                              # the per-head variant and the recall diagnostic as well
+            rec = r.recall(0)
+            idx_head = r.make_idx_head()
+            r.select_per_head(0, idx_head)
+            r.sparse_per_head(1, idx_head)
+            torch.cuda.synchronize()
+            idx, cnt, ih = r.idx.cpu().numpy(), r.cnt.cpu().numpy(), idx_head.cpu().numpy()
+            out = bf16_bits(r.outs[1])
+            for b in range(B):
+                q, Kc, _ = host_view(inp, 0, b)
+                rho_h = oracle.select_per_head(q, Kc, K, W, sinks)
+                assert (ih[b, :, : cnt[b]] == rho_h).all(), f"case {case}: per-head sets differ, seq {b}"
+                np.testing.assert_allclose(rec[b].cpu().numpy(), oracle.recall(q, Kc, idx[b, : cnt[b]]), atol=1e-3, rtol=0)
+                q, Kc, Vc = host_view(inp, 1, b)
+                assert_close_bf16(out[b], oracle.attention_per_head(q, Kc, Vc, rho_h), f"case {case}: per-head attention seq {b}")
