@@ -388,13 +388,14 @@ __device__ __forceinline__ uint32_t dpp_u32(uint32_t old, uint32_t v) {
 }
 template <int STRIDE>
 __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
-    // every lane is written, so the "old" operand is arbitrary: passing v itself saves a move
-    if constexpr (STRIDE == 1) return dpp_u32<0xB1>(v, v);             // quad_perm [1,0,3,2]
-    else if constexpr (STRIDE == 2) return dpp_u32<0x4E>(v, v);        // quad_perm [2,3,0,1]
+    // every lane has a source lane, so a plain DPP move into a fresh register does it (one
+    // instruction, no copy of the destination's previous value)
+    if constexpr (STRIDE == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);        // quad_perm [1,0,3,2]
+    else if constexpr (STRIDE == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
     else if constexpr (STRIDE == 4) {
         const uint32_t t = dpp_u32<0x104, 0x5>(v, v);                 // row_shl:4 into lanes 0-3, 8-11 of a row
         return dpp_u32<0x114, 0xA>(t, v);                             // row_shr:4 into lanes 4-7, 12-15
-    } else if constexpr (STRIDE == 8) return dpp_u32<0x128>(v, v);     // row_ror:8
+    } else if constexpr (STRIDE == 8) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true);   // row_ror:8
     else if constexpr (STRIDE == 16) {
         const auto s = __builtin_amdgcn_permlane16_swap(v, v, false, false);   // s[0]: rows 0,0,2,2; s[1]: rows 1,1,3,3
         return (threadIdx.x & 16) ? s[0] : s[1];
