@@ -174,6 +174,15 @@ cusa_status cusa_attention_recall(const cusa_params* params, const void* q, cons
 cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_kv* kv,
                            void* out, void* ws, size_t ws_bytes, void* stream);
 
+/* A selection layer in one call (the selection branch of Alg. 1): out = FullAttention(q, C[:])
+ * and rho = the selection of cusa_select, from one pass over K (the pass that computes the
+ * output also writes the scores).  idx and cnt as in cusa_select (bit for bit the same rho);
+ * out as in cusa_full_attn up to binary32 rounding order.  This is what cusa_decode_step runs
+ * for a SELECT layer; a caller that drives the layers itself uses it instead of
+ * cusa_full_attn followed by cusa_select, which read K twice. */
+cusa_status cusa_select_layer(const cusa_params* params, const void* q, const cusa_kv* kv, void* out,
+                              int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream);
+
 /* Attention part of one decode step of Alg. 1 over n_layers layers.
  * layer_kind  host int32[n_layers] of cusa_layer_kind.  FULL: full attention.
  *             SELECT: full attention for this layer's output, then rho is rebuilt

@@ -22,7 +22,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_LAUNCH = rang
 
 EXPORTS = [
     "cusa_workspace_bytes", "cusa_workspace_layout", "cusa_select", "cusa_sparse_attn",
-    "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall",
+    "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall", "cusa_select_layer",
     "cusa_full_attn", "cusa_decode_step", "cusa_strerror", "cusa_profile_num_kernels",
     "cusa_profile_kernel_name", "cusa_profile_enable", "cusa_profile_reset", "cusa_profile_read",
 ]
@@ -78,10 +78,11 @@ def load():
     lib.cusa_select_per_head.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, sz, vp]
     lib.cusa_sparse_attn_per_head.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, vp, sz, vp]
     lib.cusa_attention_recall.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, i32, vp, vp, sz, vp]
+    lib.cusa_select_layer.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, vp, sz, vp]
     lib.cusa_full_attn.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, sz, vp]
     lib.cusa_decode_step.argtypes = [P(CusaParams), i32, P(i32), P(vp), P(CusaKv), P(vp), vp, vp, vp, sz, vp]
     for name in ("cusa_workspace_bytes", "cusa_workspace_layout", "cusa_select", "cusa_sparse_attn",
-                 "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall",
+                 "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall", "cusa_select_layer",
                  "cusa_full_attn", "cusa_decode_step", "cusa_profile_read"):
         getattr(lib, name).restype = ctypes.c_int
     lib.cusa_strerror.argtypes = [ctypes.c_int]
@@ -191,6 +192,13 @@ def attention_recall(params: CusaParams, q, kv: KvCache, idx, cnt, recall, ws, p
     _check(load().cusa_attention_recall(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx), _ptr(cnt),
                                         1 if per_head else 0, _ptr(recall), _ptr(ws), ws.numel(), _stream()),
            "cusa_attention_recall")
+
+
+def select_layer(params: CusaParams, q, kv: KvCache, out, idx, cnt, ws):
+    """A selection layer in one call: full-attention output and rho from one pass over K."""
+    d = kv.desc()
+    _check(load().cusa_select_layer(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(out), _ptr(idx), _ptr(cnt),
+                                    _ptr(ws), ws.numel(), _stream()), "cusa_select_layer")
 
 
 def full_attn(params: CusaParams, q, kv: KvCache, out, ws):

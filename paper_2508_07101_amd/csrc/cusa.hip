@@ -497,6 +497,21 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
     return launch_status();
 }
 
+// A selection layer (Alg. 1): full attention for the layer's output and rho from the same q and K.
+// The pass over all tokens also writes the scores, so K is read once.
+cusa_status run_select_layer(const cusa_params* p, const void* q, const cusa_kv* kv, void* out, int32_t* idx,
+                             int32_t* cnt, void* ws, const WsLayout& w, hipStream_t s) {
+    ScoreOut score;
+    if (kv->max_seq_len > p->budget) {
+        score.P = ws_ptr<float>(ws, w.scores);
+        score.ldp = w.ldp;
+        score.window = p->window;
+    }
+    cusa_status st = run_attention<false>(p, q, kv, nullptr, nullptr, kv->max_seq_len, out, ws, w, s, score);
+    if (st != CUSA_OK) return st;
+    return run_select(p, q, kv, idx, cnt, ws, w, s, score.P != nullptr);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -608,6 +623,18 @@ cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_
                                 static_cast<hipStream_t>(stream));
 }
 
+cusa_status cusa_select_layer(const cusa_params* params, const void* q, const cusa_kv* kv, void* out, int32_t* idx,
+                              int32_t* cnt, void* ws, size_t ws_bytes, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !out || !idx || !cnt || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    if ((st = check_select_length(params, kv)) != CUSA_OK) return st;
+    const WsLayout w = make_layout(params, kv->max_seq_len);
+    if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
+    return run_select_layer(params, q, kv, out, idx, cnt, ws, w, static_cast<hipStream_t>(stream));
+}
+
 cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const int32_t* layer_kind,
                              const void* const* q_layers, const cusa_kv* kv_layers, void* const* out_layers,
                              int32_t* idx, int32_t* cnt, void* ws, size_t ws_bytes, void* stream) {
@@ -641,18 +668,10 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
         if (layer_kind[i] == CUSA_LAYER_SPARSE) {
             const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
             st = run_attention<true>(params, q_layers[i], kv, idx, cnt, n_max, out_layers[i], ws, w, s);
+        } else if (layer_kind[i] == CUSA_LAYER_SELECT) {
+            st = run_select_layer(params, q_layers[i], kv, out_layers[i], idx, cnt, ws, w, s);
         } else {
-            // a selection layer's pass over all tokens also writes the scores: K is read once
-            ScoreOut score;
-            if (layer_kind[i] == CUSA_LAYER_SELECT && kv->max_seq_len > params->budget) {
-                score.P = ws_ptr<float>(ws, w.scores);
-                score.ldp = w.ldp;
-                score.window = params->window;
-            }
-            st = run_attention<false>(params, q_layers[i], kv, nullptr, nullptr, kv->max_seq_len, out_layers[i], ws,
-                                      w, s, score);
-            if (st == CUSA_OK && layer_kind[i] == CUSA_LAYER_SELECT)
-                st = run_select(params, q_layers[i], kv, idx, cnt, ws, w, s, score.P != nullptr);
+            st = run_attention<false>(params, q_layers[i], kv, nullptr, nullptr, kv->max_seq_len, out_layers[i], ws, w, s);
         }
         if (st != CUSA_OK) return st;
     }

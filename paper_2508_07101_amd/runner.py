@@ -55,6 +55,10 @@ class StepRunner:
     def select(self, layer_pos: int):
         cb.select(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt, self.ws)
 
+    def select_layer(self, layer_pos: int):
+        cb.select_layer(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.idx,
+                        self.cnt, self.ws)
+
     def sparse(self, layer_pos: int):
         cb.sparse_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt,
                        self.outs[layer_pos], self.ws)

@@ -104,6 +104,9 @@ def test_per_head_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.cusa_select_per_head(ctypes.byref(p), fake, ctypes.byref(lng), fake, fake, fake, 1 << 40, None) == cb.ERR_UNSUPPORTED
     assert lib.cusa_sparse_attn_per_head(ctypes.byref(p), fake, ctypes.byref(kv), fake, None, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_sparse_attn_per_head(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    assert lib.cusa_select_layer(ctypes.byref(p), fake, ctypes.byref(kv), None, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_select_layer(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
+    assert lib.cusa_select_layer(ctypes.byref(p), fake, ctypes.byref(lng), fake, fake, fake, fake, 1 << 40, None) == cb.ERR_UNSUPPORTED
     assert lib.cusa_attention_recall(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, 0, None, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_attention_recall(ctypes.byref(p), fake, ctypes.byref(kv), fake, fake, 1, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
     bad = cb.CusaKv(0x1000, 0x2000, cb.KV_CONTIGUOUS, 0, 4096 * 128, 64, None, 0, 0, 0, 0x3000, 4096)

@@ -458,6 +458,29 @@ def test_decode_loop_first_selection_feeds_the_layers_before_the_reselection():
         assert_close_bf16(out[b], oracle.attention(q, K, V, rho1), f"layer 2 seq {b}")
 
 
+@pytest.mark.parametrize("paged", [False, True])
+def test_selection_layer_entry_point_equals_the_decode_step(paged):
+    """cusa_select_layer + cusa_sparse_attn, called layer by layer, give what cusa_decode_step gives."""
+    w = small("layercall", batch=3, seq_len=2300, lengths=(2300, 180, 1290), paged=paged, n_planted=4, n_sink=4)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.run()
+    torch.cuda.synchronize()
+    idx, cnt, outs = r.idx.clone(), r.cnt.clone(), [o.clone() for o in r.outs]
+    r.idx.fill_(-1)
+    for o in r.outs:
+        o.zero_()
+    r.select_layer(0)
+    r.sparse(1)
+    torch.cuda.synchronize()
+    assert torch.equal(r.cnt, cnt)
+    for b in range(w.batch):
+        assert torch.equal(r.idx[b, : int(cnt[b])], idx[b, : int(cnt[b])])
+    assert torch.equal(r.outs[0], outs[0]) and torch.equal(r.outs[1], outs[1])
+    check_select(inp, r, 0)
+    check_attention(inp, r, 0, LAYER_SELECT)
+
+
 def test_strided_contiguous_cache_view():
     """K/V given as [B, L, G, d] storage viewed as [B, G, L, d] (token stride G*d)."""
     w = small("strided", batch=2, seq_len=900)
