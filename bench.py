@@ -29,7 +29,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "loop"],
                     help="c1..c5: one decode step at fixed lengths (c2 is the configuration the metric is quoted on); "
                          "loop: consecutive decode steps, every sequence one token longer after each")
