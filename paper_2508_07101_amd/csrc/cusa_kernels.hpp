@@ -110,17 +110,19 @@ __global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t*
                                                                   int budget, int window, int tiles_per_seq,
                                                                   int n_tiles, KvView kv) {
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
-    constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
     constexpr int QL = (GQ * D * 2 + 1023) / 1024;    // 16-byte q loads per lane
     __shared__ u32x4 tile_all[SCORE_WAVES][SCORE_ROWS * 16];
-    __shared__ __attribute__((aligned(16))) uint16_t q_all[SCORE_WAVES][SETS * 4 * QSB];
+    // q of the wave's current group as binary32, [head][128], ready for the product chain.  The
+    // 8-float group g of head h sits at group g ^ (h & 3), so that the four heads a quad of lanes
+    // reads at once come from different banks without padding the rows.
+    __shared__ __attribute__((aligned(16))) float q_all[SCORE_WAVES][SETS * 4 * D];
     const int lane = threadIdx.x & 63, r = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     u32x4* const tile = tile_all[wave];
-    uint16_t* const qs = q_all[wave];
+    float* const qs = q_all[wave];
     const int G = kv.G;
     const int stride = gridDim.x * SCORE_WAVES;
-    for (int i = lane; i < SETS * 4 * QSB / 2; i += 64) reinterpret_cast<uint32_t*>(qs)[i] = 0u;   // heads beyond GQ contribute zeros
+    for (int i = lane; i < SETS * 4 * D; i += 64) qs[i] = 0.0f;   // heads beyond GQ contribute zeros
 
     // next tile at or after `id` (stride: all waves of the grid) that has candidates; n_tiles if none
     auto next_valid = [&](int id, int& b, int& kvh, int& t0, int& Lc) __attribute__((always_inline)) {
@@ -174,8 +176,13 @@ __global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t*
                 float qf[SETS][8];
 #pragma unroll
                 for (int s = 0; s < SETS; ++s) {
-                    const u32x4 qw = *reinterpret_cast<const u32x4*>(&qs[(s * 4 + (lane & 3)) * QSB + cc * 8]);
-                    unpack8(make_uint4(qw.x, qw.y, qw.z, qw.w), qf[s]);
+                    const float* const src = &qs[(s * 4 + (lane & 3)) * D + ((cc ^ (lane & 3)) << 3)];
+                    const f32x4 qa = *reinterpret_cast<const f32x4*>(src), qb = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        qf[s][e] = qa[e];
+                        qf[s][4 + e] = qb[e];
+                    }
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -203,7 +210,14 @@ __global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t*
 #pragma unroll
             for (int j = 0; j < QL; ++j) {
                 const int e0 = (j * 64 + lane) * 8;   // first of the lane's 8 consecutive elements of the group's q
-                if (e0 < GQ * D) *reinterpret_cast<u32x4*>(&qs[(e0 >> 7) * QSB + (e0 & (D - 1))]) = qstage[j];
+                if (e0 < GQ * D) {
+                    const int hd = e0 >> 7, grp = (e0 & (D - 1)) >> 3;
+                    float wide[8];
+                    unpack8(make_uint4(qstage[j].x, qstage[j].y, qstage[j].z, qstage[j].w), wide);
+                    float* const dst = &qs[hd * D + ((grp ^ (hd & 3)) << 3)];
+                    *reinterpret_cast<f32x4*>(dst) = f32x4{wide[0], wide[1], wide[2], wide[3]};
+                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{wide[4], wide[5], wide[6], wide[7]};
+                }
             }
             qb = nb;
             qkvh = nkvh;
