@@ -672,3 +672,30 @@ def test_random_small_configurations():
                 np.testing.assert_allclose(rec[b].cpu().numpy(), oracle.recall(q, Kc, idx[b, : cnt[b]]), atol=1e-3, rtol=0)
                 q, Kc, Vc = host_view(inp, 1, b)
                 assert_close_bf16(out[b], oracle.attention_per_head(q, Kc, Vc, rho_h), f"case {case}: per-head attention seq {b}")
+
+
+def test_decode_step_captured_in_a_hip_graph_replays_like_the_eager_step():
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a step can be
+    captured once and replayed; every replay must give what the eager step gives."""
+    w = small("graph", n_layers=4, schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SPARSE), batch=3,
+              seq_len=2600, lengths=(2600, 140, 1777), paged=True, n_planted=4, n_sink=4)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    r.run()                                            # eager: also warms the library (LDS attributes) before capture
+    torch.cuda.synchronize()
+    want_idx, want_outs = r.idx.clone(), [o.clone() for o in r.outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r.run()
+    for replay in range(3):
+        r.idx.fill_(-1)                                # eager work between the replays
+        for o in r.outs:
+            o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for b in range(w.batch):
+            n = int(r.cnt[b])
+            assert torch.equal(r.idx[b, :n], want_idx[b, :n]), f"replay {replay}: rho differs, seq {b}"
+        for got, ref in zip(r.outs, want_outs):
+            assert torch.equal(got, ref), f"replay {replay}: outputs differ"
