@@ -699,3 +699,23 @@ def test_decode_step_captured_in_a_hip_graph_replays_like_the_eager_step():
             assert torch.equal(r.idx[b, :n], want_idx[b, :n]), f"replay {replay}: rho differs, seq {b}"
         for got, ref in zip(r.outs, want_outs):
             assert torch.equal(got, ref), f"replay {replay}: outputs differ"
+
+
+def test_sparse_attention_clamps_indices_outside_the_sequence():
+    """idx entries must lie in [0, L) (the caller's duty); the kernel still never reads outside the cache:
+    it clamps, so the result is attention over the clamped list."""
+    w = small("clamp", batch=2, seq_len=900, lengths=(900, 650), budget=64, window=16)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    rng = np.random.default_rng(9)
+    idx = np.stack([np.sort(rng.choice(L, size=64, replace=False)) for L in inp.seq_lens_host]).astype(np.int32)
+    idx[0, :3] = (-7, -1, -2_000_000_000)
+    idx[1, -2:] = (650, 2_000_000_000)
+    r.idx.copy_(torch.from_numpy(idx))
+    r.cnt.fill_(64)
+    r.sparse(1)
+    torch.cuda.synchronize()
+    out = bf16_bits(r.outs[1])
+    for b, L in enumerate(inp.seq_lens_host):
+        q, K, V = host_view(inp, 1, b)
+        assert_close_bf16(out[b], oracle.attention(q, K, V, np.clip(idx[b], 0, L - 1)), f"clamped list, seq {b}")
