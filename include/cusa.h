@@ -13,7 +13,16 @@
  *    until the work enqueued on `stream` has finished.
  *  - Calls only ENQUEUE kernels on `stream` (a hipStream_t passed as void*,
  *    NULL = the default stream).  They never allocate, free or synchronise, so
- *    a caller may capture them into a HIP graph.
+ *    a caller may capture them into a HIP graph.  One exception, once per
+ *    device: the first library call made with a device current sets that
+ *    device's kernel attributes (LDS limits) and looks up the library's own
+ *    device symbols -- host-side calls that enqueue nothing.  Every caller
+ *    sizes its workspace with cusa_workspace_bytes before anything else, and
+ *    that call does this set-up; a capture therefore never sees it, provided
+ *    cusa_workspace_bytes has run on that device beforehand.
+ *  - The per-kernel timing facility at the end of this header is the other
+ *    exception: while it is enabled the library creates HIP events and keeps
+ *    host-side records, so it must be off under graph capture.
  *  - Argument errors are detected on the host before anything is enqueued and
  *    returned as a cusa_status; no C++ exception crosses this boundary.  A
  *    failed kernel launch returns CUSA_ERR_LAUNCH.
@@ -55,7 +64,7 @@ typedef enum { CUSA_KV_CONTIGUOUS = 0, CUSA_KV_PAGED = 1 } cusa_kv_layout;
  * (descending), then by position.  Both keep the first K-W of that order. */
 typedef enum { CUSA_RANK_FIRST_OCCURRENCE = 0, CUSA_RANK_VOTES = 1, CUSA_RANK_MAX_SCORE = 2 } cusa_rank_mode;
 
-/* Problem statement of Alg. 1 ("token budget K, static ratio r"), host memory. */
+/* Problem statement of Alg. 1 (its inputs: the token budget and the recency ratio), host memory. */
 typedef struct {
     int32_t batch;          /* B sequences, each with its own rho                              */
     int32_t n_q_heads;      /* H                                                               */
@@ -202,6 +211,10 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
 
 const char* cusa_strerror(cusa_status status);
 
+/* Digest of the sources this binary was compiled from (16 hex digits); a loader compares it
+ * with the sources it sees to tell a stale binary. */
+const char* cusa_build_id(void);
+
 /* ---- per-kernel timing (benchmark support; not part of the method) ---------
  * While enabled, every kernel the library enqueues is launched with a start and a
  * stop event that the runtime fills from the dispatch's own begin and end time
@@ -209,12 +222,22 @@ const char* cusa_strerror(cusa_status status);
  * cusa_profile_read waits for those events and returns, for kernel id i < n, the
  * number of launches and the summed milliseconds since the last reset.  Enabling
  * costs host time per launch and creates events, so it must not be on under graph
- * capture.  cusa_profile_num_kernels returns the number of kernel ids. */
+ * capture.  cusa_profile_num_kernels returns the number of kernel ids.
+ * The facility holds process-wide state behind a mutex (event pool, pending records, totals);
+ * with it off the library keeps no state beyond the once-per-device set-up described above. */
 int32_t     cusa_profile_num_kernels(void);
 const char* cusa_profile_kernel_name(int32_t id);
 void        cusa_profile_enable(int32_t on);
 void        cusa_profile_reset(void);
 cusa_status cusa_profile_read(int32_t n, int64_t* calls, double* total_ms);
+
+/* Streaming-read probe (benchmark support; not part of the method): enqueues one kernel that
+ * reads `bytes` bytes (a multiple of 16 is read; at least 16) of device memory `src` (16-byte
+ * aligned) with plain coalesced 16-byte loads and folds them; `sink` is 4 bytes of device memory
+ * the kernel may write.  Timed through the facility above (kernel "probe_stream_read_kernel"),
+ * it gives the read rate a pure streaming pass reaches on the machine -- the practical ceiling
+ * beside the nominal HBM peak.  Errors: INVALID_ARG, LAUNCH. */
+cusa_status cusa_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

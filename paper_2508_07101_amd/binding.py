@@ -25,6 +25,7 @@ EXPORTS = [
     "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall", "cusa_select_layer",
     "cusa_full_attn", "cusa_decode_step", "cusa_strerror", "cusa_profile_num_kernels",
     "cusa_profile_kernel_name", "cusa_profile_enable", "cusa_profile_reset", "cusa_profile_read",
+    "cusa_build_id", "cusa_probe_stream_read",
 ]
 
 
@@ -61,13 +62,33 @@ def lib_path() -> str:
     return _build.LIB
 
 
+def built_from() -> str:
+    """Build id of the library file, read from the file itself (nothing is mapped)."""
+    marker = b"CUSA_BUILD_ID="
+    with open(_build.LIB, "rb") as fh:
+        data = fh.read()
+    at = data.find(marker)
+    if at < 0:
+        return "none"
+    return data[at + len(marker): at + len(marker) + 16].decode("ascii", "replace")
+
+
 def load():
-    """Load the built library (building it first only when none exists)."""
+    """Load the built library.  It is built first when none exists, and rebuilt when the file found
+    was compiled from other sources than those in the tree (its build id says so); if that rebuild
+    is impossible the call raises rather than run kernels that do not match the sources."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build_lib(force=False)
+    have, want = built_from(), _build.source_id()
+    if have != want:
+        try:
+            _build.build_lib(force=True)
+        except Exception as e:
+            raise RuntimeError(f"libcusa.so was built from other sources (build id {have}, tree {want}) "
+                               f"and cannot be rebuilt here: {e}; run __graft_entry__.build()") from e
     lib = ctypes.CDLL(_build.LIB)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     P = ctypes.POINTER
@@ -93,6 +114,9 @@ def load():
     lib.cusa_profile_enable.argtypes = [i32]
     lib.cusa_profile_reset.argtypes = []
     lib.cusa_profile_read.argtypes = [i32, P(ctypes.c_int64), P(ctypes.c_double)]
+    lib.cusa_build_id.restype = ctypes.c_char_p
+    lib.cusa_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.cusa_probe_stream_read.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -230,6 +254,12 @@ class DecodeStep:
 
 def decode_step(params, layer_kind, q_layers, kv_layers, out_layers, idx, cnt, ws):
     DecodeStep(params, layer_kind, q_layers, kv_layers, out_layers, idx, cnt, ws).run()
+
+
+def probe_stream_read(src: torch.Tensor, sink: torch.Tensor):
+    """Enqueue the streaming-read probe over the bytes of src (benchmark support)."""
+    _check(load().cusa_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()),
+           "cusa_probe_stream_read")
 
 
 # ---- per-kernel timing ---------------------------------------------------------

@@ -1,6 +1,7 @@
 """Builds libcusa.so (gfx950) in-tree from csrc/ with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import shutil
 import subprocess
@@ -29,11 +30,15 @@ def hipcc() -> str:
     return exe
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+def source_id() -> str:
+    """Digest of everything the library is compiled from (sources, headers, flags); the library
+    carries the digest it was built from (cusa_build_id), which is how a stale binary is told."""
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()[:16]
 
 
 def build_lib(force: bool = True, extra_flags=()) -> str:
@@ -41,7 +46,7 @@ def build_lib(force: bool = True, extra_flags=()) -> str:
     if not force and os.path.exists(LIB):
         return LIB
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *SOURCES]
+    cmd = [hipcc(), *HIPCC_FLAGS, f'-DCUSA_BUILD_ID="{source_id()}"', *extra_flags, "-o", tmp, *SOURCES]
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
     return LIB

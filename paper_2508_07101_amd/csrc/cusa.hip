@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -18,11 +19,11 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
-                                             "rank_aggregate_kernel", "recall_kernel"};
+                                             "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -33,7 +34,7 @@ struct ProfRec {
 };
 struct Profiler {
     std::mutex mu;
-    bool on = false;
+    std::atomic<bool> on{false};
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> pool;
     int64_t calls[KID_COUNT] = {0};
@@ -47,7 +48,10 @@ hipEvent_t prof_event() {
         return e;
     }
     hipEvent_t e = nullptr;
-    (void)hipEventCreate(&e);
+    if (hipEventCreate(&e) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
     return e;
 }
 
@@ -59,7 +63,7 @@ struct same_as { using type = T; };
 template <typename... KArgs>
 void launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem, hipStream_t s,
             typename same_as<KArgs>::type... args) {
-    if (!g_prof.on) {
+    if (!g_prof.on.load(std::memory_order_acquire)) {
         kernel<<<grid, block, shmem, s>>>(args...);
         return;
     }
@@ -69,6 +73,15 @@ void launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shm
         std::lock_guard<std::mutex> lk(g_prof.mu);
         rec.start = prof_event();
         rec.stop = prof_event();
+        if (!rec.start || !rec.stop) {                // no events to be had: launch untimed
+            if (rec.start) g_prof.pool.push_back(rec.start);
+            if (rec.stop) g_prof.pool.push_back(rec.stop);
+            rec.start = rec.stop = nullptr;
+        }
+    }
+    if (!rec.start) {
+        kernel<<<grid, block, shmem, s>>>(args...);
+        return;
     }
     hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, s, rec.start, rec.stop, 0, args...);
     std::lock_guard<std::mutex> lk(g_prof.mu);
@@ -174,6 +187,17 @@ AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
     return pl;
 }
 
+// Upper bound of plan_attn(m, BG', g).n_splits over every m <= n_max and BG' >= BG: with the chunk
+// below its cap a token list is cut into at most ceil(TARGET_WGS / BG) pieces, at the cap into
+// ceil(m / CHUNK_CAP).  Monotone in n_max, so a workspace sized for a capacity serves every
+// shorter bound.
+int max_splits_bound(int n_max, int BG) {
+    const int by_wgs = (TARGET_WGS + BG - 1) / BG;
+    const int by_cap = (n_max + CHUNK_CAP - 1) / CHUNK_CAP;
+    const int m = by_wgs > by_cap ? by_wgs : by_cap;
+    return m < MAX_SPLITS ? m : MAX_SPLITS;
+}
+
 struct WsLayout {
     size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, lse, out_tmp, total;
     int64_t ldp;
@@ -190,9 +214,8 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     w.ldp = (lc + 63) / 64 * 64;
     w.k = resolved_k(p);
     if (w.k < 1) w.k = 1;
-    int ms = plan_attn(max_seq_len, BG, g).n_splits;
-    int ms2 = plan_attn(p->budget > 0 ? p->budget : 1, BG, g).n_splits;
-    w.max_splits = ms > ms2 ? ms : ms2;
+    (void)g;
+    w.max_splits = max_splits_bound(max_seq_len > p->budget ? max_seq_len : p->budget, BG);
     size_t off = 0;
     w.scores = off;    off += align256((size_t)(B * H * w.ldp) * 4);
     w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);
@@ -209,10 +232,12 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     return w;
 }
 
+bool device_ready();
+
 cusa_status check_ws(const WsLayout& w, void* ws, size_t ws_bytes) {
     if (!ws || ((uintptr_t)ws & 255)) return CUSA_ERR_INVALID_ARG;
     if (ws_bytes < w.total) return CUSA_ERR_WORKSPACE_TOO_SMALL;
-    return CUSA_OK;
+    return device_ready() ? CUSA_OK : CUSA_ERR_LAUNCH;
 }
 
 // The union kernel's bitmap over candidate positions has to fit LDS.
@@ -366,29 +391,59 @@ cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cu
     return launch_status();
 }
 
-// LDS beyond 48 KB per workgroup has to be granted per kernel; remembered per kernel so the
-// runtime is asked once.
+// LDS beyond 48 KB per workgroup has to be granted per kernel and per device.  All kernels that
+// can ask for more are granted their maximum once per device, outside any enqueueing work: on the
+// first library call made with that device current (cusa_workspace_bytes included), so that later
+// calls only enqueue kernels.
+constexpr size_t SEL_LDS_MAX = (size_t)UNION_MAX_POSITIONS / 8;   // the selection bitmaps
 
-bool allow_dynamic_lds(const void* fn, size_t bytes) {
-    static std::mutex mu;
-    static std::vector<std::pair<const void*, size_t>> granted;
-    std::lock_guard<std::mutex> lk(mu);
-    for (auto& g : granted)
-        if (g.first == fn && g.second >= bytes) return true;
+template <int ITEMS, int MTOP>
+constexpr size_t topk_lds_bytes() {
+    return ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
+}
+
+bool grant_lds(const void* fn, size_t bytes) {
+    if (bytes <= 48 * 1024) return true;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
-    granted.emplace_back(fn, bytes);
     return true;
+}
+
+template <int ITEMS>
+bool grant_topk_items() {
+    return grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 1>), topk_lds_bytes<ITEMS, 1>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 2>), topk_lds_bytes<ITEMS, 2>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 4>), topk_lds_bytes<ITEMS, 4>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8>), topk_lds_bytes<ITEMS, 8>());
+}
+
+constexpr int MAX_DEVICES = 64;
+
+// True once the current device's kernels hold their LDS grants.  Without a device (a host that
+// only sizes workspaces) nothing is done and false is returned.
+bool device_ready() {
+    static std::mutex mu;
+    static bool ready[MAX_DEVICES] = {false};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        return false;
+    }
+    std::lock_guard<std::mutex> lk(mu);
+    if (ready[dev]) return true;
+    const bool ok = grant_topk_items<4>() && grant_topk_items<8>() && grant_topk_items<16>() && grant_topk_items<32>() &&
+                    grant_topk_items<0>() && grant_lds(reinterpret_cast<const void*>(union_kernel), SEL_LDS_MAX) &&
+                    grant_lds(reinterpret_cast<const void*>(per_head_rho_kernel), SEL_LDS_MAX);
+    ready[dev] = ok;
+    return ok;
 }
 
 template <int ITEMS, int MTOP>
 cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
                           int32_t* rho_head, int H, int k, int budget, int window, int raw, int n_sink) {
-    const size_t shmem = ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
-    if (shmem > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, MTOP>), shmem))
-        return CUSA_ERR_LAUNCH;
+    const size_t shmem = topk_lds_bytes<ITEMS, MTOP>();
     launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
     return launch_status();
 }
@@ -477,20 +532,15 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
                                                 rho_rank, n_hist, p->budget, p->window, 1, p->n_sink);
                 if (st != CUSA_OK) return st;
             }
-            if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
-                return CUSA_ERR_LAUNCH;
             launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(1, B), SEL_THREADS, bitmap, s, rho_rank, kv->seq_lens, idx, cnt, 1,
                    n_hist, p->budget, p->window, p->n_sink);
             return launch_status();
         }
         if (per_head) {
-            if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(per_head_rho_kernel), bitmap))
-                return CUSA_ERR_LAUNCH;
             launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(H, B), SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H,
                    w.k, p->budget, p->window, p->n_sink);
             return launch_status();
         }
-        if (bitmap > 48 * 1024 && !allow_dynamic_lds(reinterpret_cast<const void*>(union_kernel), bitmap)) return CUSA_ERR_LAUNCH;
         launch(KID_UNION, union_kernel, B, SEL_THREADS, bitmap, s, rho_head, kv->seq_lens, idx, cnt, H, w.k, p->budget,
                p->window, p->n_sink);
     }
@@ -522,6 +572,7 @@ cusa_status cusa_workspace_bytes(const cusa_params* params, int32_t max_seq_len,
     cusa_status st = check_params(params, true);
     if (st != CUSA_OK) return st;
     if (!bytes || max_seq_len < 1) return CUSA_ERR_INVALID_ARG;
+    (void)device_ready();
     *bytes = make_layout(params, max_seq_len).total;
     return CUSA_OK;
 }
@@ -530,6 +581,7 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
     cusa_status st = check_params(params, true);
     if (st != CUSA_OK) return st;
     if (!layout || max_seq_len < 1) return CUSA_ERR_INVALID_ARG;
+    (void)device_ready();
     const WsLayout w = make_layout(params, max_seq_len);
     layout->scores_offset = w.scores;
     layout->ld_scores = w.ldp;
@@ -561,6 +613,16 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
     return run_attention<true>(params, q, kv, idx, cnt, n_max, out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+cusa_status cusa_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes < 16 || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3)) return CUSA_ERR_INVALID_ARG;
+    const int64_t n_vec = (int64_t)(bytes / 16);
+    int64_t wgs = (n_vec + PROBE_THREADS - 1) / PROBE_THREADS;
+    if (wgs > 2048) wgs = 2048;                       // 8 resident workgroups per CU
+    launch(KID_PROBE, probe_stream_read_kernel, dim3((unsigned)wgs), PROBE_THREADS, 0, static_cast<hipStream_t>(stream),
+           static_cast<const u32x4*>(src), n_vec, static_cast<uint32_t*>(sink));
+    return launch_status();
 }
 
 cusa_status cusa_select_per_head(const cusa_params* params, const void* q, const cusa_kv* kv, int32_t* idx_head,
@@ -678,12 +740,12 @@ cusa_status cusa_decode_step(const cusa_params* params, int32_t n_layers, const 
     return CUSA_OK;
 }
 
-#ifdef CUSA_TRACE
-// Development aid (only in builds with -DCUSA_TRACE): copies the in-kernel time stamps to the host.
-int cusa_debug_trace(unsigned long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(cusa::g_trace), sizeof(unsigned long long) * (size_t)n);
-}
+#ifndef CUSA_BUILD_ID
+#define CUSA_BUILD_ID "unknown"
 #endif
+// The marker also lets a loader read the id from the file without mapping the library.
+static const char kBuildId[] = "CUSA_BUILD_ID=" CUSA_BUILD_ID;
+const char* cusa_build_id(void) { return kBuildId + 14; }
 
 const char* cusa_strerror(cusa_status status) {
     switch (status) {
@@ -702,7 +764,7 @@ const char* cusa_profile_kernel_name(int32_t id) { return (id >= 0 && id < KID_C
 
 void cusa_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.on = on != 0;
+    g_prof.on.store(on != 0, std::memory_order_release);
 }
 
 static void prof_drain_locked() {

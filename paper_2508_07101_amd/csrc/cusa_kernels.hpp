@@ -4,7 +4,8 @@
 //                       layer), one lane per key row, K staged through LDS,
 //                       products accumulated by k = 1 MFMA in column order
 //   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on
-//                       order-preserving keys, then a bitonic sort in LDS
+//                       order-preserving keys, then a bitonic sort held in registers
+//                       (lane exchanges by DPP / permlane swaps, LDS across waves)
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
 //                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
 //   attn_kernel         split-K flash-decode over all tokens or over rho
@@ -15,21 +16,6 @@
 #include <stdint.h>
 
 namespace cusa {
-
-// Development aid: builds with -DCUSA_TRACE record wall-clock stamps per workgroup.
-#ifdef CUSA_TRACE
-__device__ unsigned long long g_trace[8192 * 8];
-#define CUSA_TRACE_POINT(slot)                                                                         \
-    do {                                                                                               \
-        if (threadIdx.x == 0) {                                                                        \
-            int wg_ = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);                  \
-            if (wg_ < 8192) g_trace[wg_ * 8 + (slot)] = wall_clock64();                                \
-        }                                                                                              \
-    } while (0)
-#else
-#define CUSA_TRACE_POINT(slot) do {} while (0)
-#endif
-
 
 constexpr int D = 128;        // head_dim
 constexpr int PAGE = 16;      // tokens per page of a paged cache
@@ -91,7 +77,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // addition per instruction, so walking the 128 columns in order is the left-to-right
 // binary32 sum the selection's bit-exactness rests on -- no reordering inside the
 // instruction can occur.  (Checked bit for bit against a scalar fmaf chain on the device.)
-// q sits in LDS as bf16, head stride padded to 136 elements (distinct banks per head).
+// q sits in LDS as binary32, one copy per wave, widened once when the wave moves to another
+// group; the 8-float groups of a head are XOR-swizzled by the head number (distinct banks for
+// the four heads a quad of lanes reads, without padding).
 //
 // Wave number v of the grid walks tiles id = v, v + waves, ... (id = (sequence, KV head, tile)
 // in that order) and issues the loads of its next tile before it scores the current one.
@@ -451,8 +439,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     // the first n_sink positions are kept in rho anyway and are no candidates (key 0, like the padding)
     const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
     const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
-
-    CUSA_TRACE_POINT(0);
     // raw_keys: the row already holds order-preserving uint32 keys (the aggregated ranking keys of
     // the votes / max-score readings) instead of binary32 scores
     auto key_of = [raw_keys](float v) { return raw_keys ? __float_as_uint(v) : score_key(v); };
@@ -526,7 +512,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     uint32_t top[MG];
 #pragma unroll
     for (int j = 0; j < MG; ++j) top[j] = 0u;
-    CUSA_TRACE_POINT(1);
     if constexpr (ITEMS > 0) {
         scan([&](uint32_t key, int) {
             uint32_t x = key;
@@ -556,8 +541,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     pick_digit<2048>(hist, scratch, &st, 21);
     const uint32_t d0 = st.prefix >> 21;
     __syncthreads();
-
-    CUSA_TRACE_POINT(2);
     // 1-3 for candidates delivered by scan_fn: the remaining digits of the k_eff-th best score key
     // T (its top digit is already in st), the position bound among the keys equal to T when they
     // straddle the cut (rare), and the survivors' composites compacted into sort_buf in any order.
@@ -567,7 +550,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         const uint32_t T = st.prefix;
         const int need_eq = st.need, count_eq = st.count_eq;
         __syncthreads();
-        CUSA_TRACE_POINT(3);
         uint32_t pos_bound = 0xffffffffu;              // take every tie
         if (count_eq > need_eq) {
             radix_select(0, need_eq, 0u, scan_fn,
@@ -576,7 +558,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
             pos_bound = ~st.prefix;                    // need_eq-th smallest tying position
             __syncthreads();
         }
-        CUSA_TRACE_POINT(4);
         if (threadIdx.x == 0) n_out = 0;
         __syncthreads();                               // also: histogram no longer needed
         // one reservation per wave: count this thread's survivors, scan the counts over the wave
@@ -667,7 +648,6 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     } else {
         finish(scan);
     }
-    CUSA_TRACE_POINT(5);
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
     // Bitonic network over NSORT = MTOP * 1024 composites, MTOP per thread in registers:
@@ -726,13 +706,10 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         for (int j = 0; j < MTOP; ++j) sort_buf[base + j * 64] = v[j];
         __syncthreads();
     }
-
-    CUSA_TRACE_POINT(6);
     // 4. rank-major output
     int32_t* __restrict__ out = rho_head + (int64_t)b * k * H + h;
     for (int j = threadIdx.x; j < k_eff; j += SEL_THREADS)
         out[(int64_t)j * H] = (int32_t)~(uint32_t)sort_buf[j];
-    CUSA_TRACE_POINT(7);
 }
 
 // ---------------------------------------------------------------- union / rank / window
@@ -802,11 +779,8 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     const int n_hist = budget - window - n_sink;      // picks to keep; the sink positions come on top
     const int32_t* __restrict__ rho = rho_head + (int64_t)b * k * H;
     const int n_words = (Lc + 31) >> 5;
-
-    CUSA_TRACE_POINT(0);
     for (int i = tid; i < n_words; i += SEL_THREADS) bits[i] = 0u;
     __syncthreads();
-    CUSA_TRACE_POINT(1);
 
     // The picks of the UNION_UNROLL slots s0 + u * 1024 + tid are requested with clamped,
     // unconditional loads (request_picks) and looked at later (take_picks: -1 past the end; a pick is
@@ -871,7 +845,6 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         }
         cum += added;
     }
-    CUSA_TRACE_POINT(2);
 
     int n_take = cum;                                  // fewer than K-W distinct picks in total (k < K-W only)
     if (crossed) {
@@ -937,9 +910,7 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
         }
         __syncthreads();
     }
-    CUSA_TRACE_POINT(3);
     n_take += emit_sinks_and_set(bits, n_words, n_sink, n_hist + n_sink, scratch, out);
-    CUSA_TRACE_POINT(4);
     for (int j = tid; j < window; j += SEL_THREADS) out[n_take + j] = L - window + j;
     if (tid == 0) cnt[b] = n_take + window;
 }
@@ -1171,8 +1142,6 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int QSF = 132;                          // padded head stride of the binary32 copy (floats)
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[SCORE ? 1 : ATTN_WAVES][SCORE ? 8 : SETS * 4 * QSB];
     __shared__ __attribute__((aligned(16))) float qf32[SCORE ? SETS * 4 * QSF : 4];
-
-    CUSA_TRACE_POINT(0);
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
@@ -1424,8 +1393,6 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         }
         wave_lds_sync();                              // the tile buffers are rewritten next iteration
     }
-
-    CUSA_TRACE_POINT(1);
     // Merge.  Inside the wave the four row groups are folded with lane swaps: of the N = 8 GQ
     // values of a lane, two folds leave N / 4 complete sums, those with flat index (head * 8 +
     // column) v0 .. v0 + N/4 - 1 where v0 depends on the row group.  The wave parks them in its
@@ -1575,6 +1542,29 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const float* __restric
         out[((int64_t)b * H + h) * D + tid] = f32_to_bf16_rne(Ls > 0.0f ? A / Ls : 0.0f);
         if (lse && tid == 0) lse[(int64_t)b * H + h] = M + log2f(Ls);
     }
+}
+
+// Streaming-read probe (benchmark support): every thread folds 16-byte loads of a plain buffer,
+// eight in flight per lane, consecutive lanes on consecutive addresses.  What this kernel reaches
+// is the practical ceiling of a read-only pass on the machine, to set beside the nominal HBM peak.
+constexpr int PROBE_THREADS = 256;
+constexpr int PROBE_UNROLL = 8;
+
+__global__ __launch_bounds__(PROBE_THREADS) void probe_stream_read_kernel(const u32x4* __restrict__ src, int64_t n_vec,
+                                                                           uint32_t* __restrict__ sink) {
+    const int64_t stride = (int64_t)gridDim.x * PROBE_THREADS;
+    u32x4 fold = {0u, 0u, 0u, 0u};
+    int64_t i = (int64_t)blockIdx.x * PROBE_THREADS + threadIdx.x;
+    for (; i + (PROBE_UNROLL - 1) * stride < n_vec; i += PROBE_UNROLL * stride) {
+        u32x4 v[PROBE_UNROLL];
+#pragma unroll
+        for (int u = 0; u < PROBE_UNROLL; ++u) v[u] = __builtin_nontemporal_load(&src[i + u * stride]);
+#pragma unroll
+        for (int u = 0; u < PROBE_UNROLL; ++u) fold ^= v[u];
+    }
+    for (; i < n_vec; i += stride) fold ^= __builtin_nontemporal_load(&src[i]);
+    const uint32_t f = fold.x ^ fold.y ^ fold.z ^ fold.w;
+    if (f == 0x9e3779b9u) *sink = f;                 // keeps the loads alive; practically never taken
 }
 
 // Attention recall (Eq. 3): the share of a head's softmax mass that falls on its token set.  With

@@ -126,3 +126,33 @@ def test_decode_step_rejects_sparse_before_select_and_unknown_kinds():
     arr = (ctypes.c_int32 * n)(cb.LAYER_SELECT, cb.LAYER_SPARSE)
     assert lib.cusa_decode_step(ctypes.byref(p), n, arr, ptrs, kvs, ptrs, fake, fake, fake, 16, None) == cb.ERR_WORKSPACE_TOO_SMALL
     assert lib.cusa_decode_step(ctypes.byref(p), 0, arr, ptrs, kvs, ptrs, fake, fake, fake, 1 << 30, None) == cb.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("B,H,G,K,W", [(1, 32, 8, 2048, 512), (1, 64, 8, 4096, 1024), (8, 32, 8, 4096, 1024),
+                                        (3, 16, 8, 256, 64), (64, 32, 8, 2048, 512)])
+def test_workspace_bytes_never_shrink_with_capacity(B, H, G, K, W):
+    """A workspace sized for a capacity must serve every shorter bound: bytes(m) <= bytes(M) for m <= M
+    (checked densely around the places where the attention kernels' tiling changes)."""
+    p = cb.make_params(B, H, G, K, W)
+    lens = sorted(set([1, 2, 63, 64, 65, 255, 256, 257, 1000] +
+                      [c + d for c in range(1024, 40000, 1024) for d in (-1, 0, 1)] +
+                      [c + d for c in (65536, 131072, 262144) for d in (-1, 0, 1)]))
+    prev = 0
+    for m in lens:
+        n = cb.workspace_bytes(p, m)
+        assert n >= prev, f"workspace shrinks from {prev} to {n} at max_seq_len {m}"
+        prev = n
+
+
+def test_build_id_matches_the_sources():
+    from paper_2508_07101_amd import build
+    assert cb.load().cusa_build_id().decode() == build.source_id() == cb.built_from()
+
+
+def test_probe_rejects_bad_arguments():
+    lib = cb.load()
+    fake = ctypes.c_void_p(0x10000)
+    assert lib.cusa_probe_stream_read(None, 1 << 20, fake, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_probe_stream_read(fake, 8, fake, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_probe_stream_read(ctypes.c_void_p(0x10008), 1 << 20, fake, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_probe_stream_read(fake, 1 << 20, None, None) == cb.ERR_INVALID_ARG
