@@ -149,6 +149,20 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
                              const int32_t* idx, const int32_t* cnt, void* out,
                              void* ws, size_t ws_bytes, void* stream);
 
+/* cusa_sparse_attn for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same result bit for bit, with the split-K partials in a static device array
+ * that is part of the library image (cusa_noalloc_max_scratch_bytes() bytes per GPU the library
+ * runs on, held until the process ends).  Arguments as cusa_sparse_attn, minus the workspace.
+ * Allocates nothing, frees nothing, synchronises nothing.
+ * Errors: as cusa_sparse_attn; UNSUPPORTED when the partials of this problem (batch * n_q_heads *
+ * splits * 520 bytes, splits as the launch plan cuts min(budget, max_seq_len) tokens) do not fit
+ * the array.  All calls on one GPU share that GPU's array: calls whose kernels may overlap (two
+ * streams, two threads) race on it and must be serialised by the caller. */
+size_t      cusa_noalloc_max_scratch_bytes(void);
+cusa_status cusa_sparse_attn_noalloc(const cusa_params* params, const void* q, const cusa_kv* kv,
+                                     const int32_t* idx, const int32_t* cnt, void* out, void* stream);
+
 /* Head-to-head selection and its sparse attention: the per-head variant the paper
  * compares CUSA with (Sec. 3.2 and the generalization figure; the per-head-index
  * kernel of the kernel-metrics table).  Every head keeps its OWN token set: its

@@ -25,7 +25,7 @@ EXPORTS = [
     "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall", "cusa_select_layer",
     "cusa_full_attn", "cusa_decode_step", "cusa_strerror", "cusa_profile_num_kernels",
     "cusa_profile_kernel_name", "cusa_profile_enable", "cusa_profile_reset", "cusa_profile_read",
-    "cusa_build_id", "cusa_probe_stream_read",
+    "cusa_build_id", "cusa_probe_stream_read", "cusa_sparse_attn_noalloc", "cusa_noalloc_max_scratch_bytes",
 ]
 
 
@@ -115,6 +115,10 @@ def load():
     lib.cusa_profile_reset.argtypes = []
     lib.cusa_profile_read.argtypes = [i32, P(ctypes.c_int64), P(ctypes.c_double)]
     lib.cusa_build_id.restype = ctypes.c_char_p
+    lib.cusa_sparse_attn_noalloc.argtypes = [P(CusaParams), vp, P(CusaKv), vp, vp, vp, vp]
+    lib.cusa_sparse_attn_noalloc.restype = ctypes.c_int
+    lib.cusa_noalloc_max_scratch_bytes.argtypes = []
+    lib.cusa_noalloc_max_scratch_bytes.restype = sz
     lib.cusa_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.cusa_probe_stream_read.restype = ctypes.c_int
     _lib = lib
@@ -195,6 +199,17 @@ def sparse_attn(params: CusaParams, q, kv: KvCache, idx, cnt, out, ws):
     d = kv.desc()
     _check(load().cusa_sparse_attn(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx), _ptr(cnt),
                                    _ptr(out), _ptr(ws), ws.numel(), _stream()), "cusa_sparse_attn")
+
+
+def sparse_attn_noalloc(params: CusaParams, q, kv: KvCache, idx, cnt, out):
+    """cusa_sparse_attn with the partials in the library's static scratch (no workspace argument)."""
+    d = kv.desc()
+    _check(load().cusa_sparse_attn_noalloc(ctypes.byref(params), _ptr(q), ctypes.byref(d), _ptr(idx), _ptr(cnt),
+                                           _ptr(out), _stream()), "cusa_sparse_attn_noalloc")
+
+
+def noalloc_max_scratch_bytes() -> int:
+    return int(load().cusa_noalloc_max_scratch_bytes())
 
 
 def select_per_head(params: CusaParams, q, kv: KvCache, idx_head, cnt, ws):

@@ -419,7 +419,13 @@ bool grant_topk_items() {
            grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8>), topk_lds_bytes<ITEMS, 8>());
 }
 
+// Split-K partials of cusa_sparse_attn_noalloc: device memory that belongs to the library image,
+// one copy per GPU, held until the process ends.  Host code never uses the array's name as an
+// address: the per-device address is asked for once (device_ready) and passed to the kernels.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
 constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
 
 // True once the current device's kernels hold their LDS grants.  Without a device (a host that
 // only sizes workspaces) nothing is done and false is returned.
@@ -436,6 +442,12 @@ bool device_ready() {
     const bool ok = grant_topk_items<4>() && grant_topk_items<8>() && grant_topk_items<16>() && grant_topk_items<32>() &&
                     grant_topk_items<0>() && grant_lds(reinterpret_cast<const void*>(union_kernel), SEL_LDS_MAX) &&
                     grant_lds(reinterpret_cast<const void*>(per_head_rho_kernel), SEL_LDS_MAX);
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return false;
+    }
+    g_scratch_ptr[dev] = ptr;
     ready[dev] = ok;
     return ok;
 }
@@ -613,6 +625,30 @@ cusa_status cusa_sparse_attn(const cusa_params* params, const void* q, const cus
     if ((st = check_ws(w, ws, ws_bytes)) != CUSA_OK) return st;
     const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
     return run_attention<true>(params, q, kv, idx, cnt, n_max, out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+size_t cusa_noalloc_max_scratch_bytes(void) { return NOALLOC_SCRATCH_BYTES; }
+
+cusa_status cusa_sparse_attn_noalloc(const cusa_params* params, const void* q, const cusa_kv* kv, const int32_t* idx,
+                                     const int32_t* cnt, void* out, void* stream) {
+    cusa_status st = check_params(params, true);
+    if (st != CUSA_OK) return st;
+    if ((st = check_kv(params, kv)) != CUSA_OK) return st;
+    if (!q || !idx || !cnt || !out || ((uintptr_t)q & 15)) return CUSA_ERR_INVALID_ARG;
+    const int n_max = params->budget < kv->max_seq_len ? params->budget : kv->max_seq_len;
+    const int g = params->n_q_heads / params->n_kv_heads, BG = params->batch * params->n_kv_heads;
+    // only the two partial arrays are laid out, for exactly the splits this launch makes
+    WsLayout w = {};
+    w.max_splits = plan_attn(n_max, BG, g).n_splits;
+    const size_t rows = (size_t)params->batch * params->n_q_heads * w.max_splits;
+    w.part_acc = 0;
+    w.part_ml = align256(rows * D * 4);
+    w.total = w.part_ml + align256(rows * 2 * 4);
+    if (w.total > NOALLOC_SCRATCH_BYTES) return CUSA_ERR_UNSUPPORTED;   // beyond the static scratch
+    if (!device_ready()) return CUSA_ERR_LAUNCH;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES || !g_scratch_ptr[dev]) return CUSA_ERR_LAUNCH;
+    return run_attention<true>(params, q, kv, idx, cnt, n_max, out, g_scratch_ptr[dev], w, static_cast<hipStream_t>(stream));
 }
 
 cusa_status cusa_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
