@@ -1,21 +1,39 @@
 #!/usr/bin/env python3
 """Benchmark of the CUSA decode hot path on one MI355X.
 
-A "step" is the attention part of one decode step of the paper's Alg. 1 over all layers of
-the workload: full-attention layers, the selection layer (full attention that also emits the
-scores + per-head top-k + cross-head union + window) and the sparse-attention layers that reuse rho.  Inputs are
-seeded, synthetic and resident in HBM before the timed region.
+A "step" is the attention part of one decode step of the paper's Alg. 1 over all layers of a
+workload: full-attention layers, the selection layer (full attention whose pass over K also emits
+the scores, then per-head top-k, cross-head union and the recency window) and the sparse-attention
+layers that reuse rho.  Inputs are seeded, synthetic and resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads c1,c2,c3,c4,c5]
 
-Prints ONE JSON line: the step time, a `roofline` object for the kernel that takes most of the
-step (algorithmic bytes / its HIP-event duration against the 8 TB/s HBM peak), per-kernel
-figures, the speedup over this library's own full attention on every layer, and `cpu_baseline`,
-the CPU oracle timed on a bounded sample of the same workload.
+One invocation measures every listed workload (default: the five quoted configurations, in that
+order) and prints ONE JSON line.  The top-level figures (`value`, `config`, `roofline`,
+`cpu_baseline`) are those of the LAST workload listed -- by default c5, the largest configuration
+one GPU holds (21.5 GB of KV cache, 6.5 GB moved per step); `configs` carries one record per
+workload with
+
+  * us_per_step: mean over the K timed steps (wall clock around exactly K steps) and the median and
+    minimum of the K step durations taken from events recorded between the steps;
+  * kernels: per kernel, launches per step and the dispatch duration (begin to end time stamp, what a
+    kernel trace reports), mean / median-free average over all launches of the K steps;
+  * rooflines: for every bandwidth-bound kernel of the step (sparse attention, the selection layer's
+    pass, plain full attention) algorithmic bytes per launch / its average duration against the
+    8 TB/s HBM peak;
+  * the same stack with full attention on every layer, and the speed-up over it;
+  * cpu_baseline: the CPU oracle timed on a bounded sample (sequence 0: one full-attention layer,
+    one selection, one sparse layer; whole step when that is short), split by stage, with the
+    core count; c1 also single-threaded.
+
+`stream_read_probe` is the read rate of a plain streaming kernel measured in the same run: the
+practical ceiling to set beside the nominal peak.
 """
 import argparse
+import ctypes
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -23,6 +41,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+QUOTED = ["c1", "c2", "c3", "c4", "c5"]
+BANDWIDTH_KERNELS = ("attn_kernel<sparse>", "attn_kernel<full+score>", "attn_kernel<full>")
 
 
 def parse():
@@ -30,9 +50,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "loop"],
-                    help="c1..c5: one decode step at fixed lengths (c2 is the configuration the metric is quoted on); "
-                         "loop: consecutive decode steps, every sequence one token longer after each")
+    ap.add_argument("--workloads", "--workload", dest="workloads", default=",".join(QUOTED),
+                    help="comma-separated list of c1..c5 and loop (consecutive decode steps, every sequence one "
+                         "token longer after each); the last one listed supplies the top-level figures")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -49,10 +69,12 @@ def parse():
                     help="skip the head-to-head comparison (every head attends its own top-k instead of the unified set)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event pass (use under rocprofv3 to keep the trace to the timed steps)")
+    ap.add_argument("--no-probe", action="store_true", help="skip the streaming-read probe")
     return ap.parse_args()
 
 
 def time_steps(fn, steps, warmup, torch):
+    """Wall clock around exactly `steps` calls, after `warmup` untimed ones; seconds per call."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -61,6 +83,19 @@ def time_steps(fn, steps, warmup, torch):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
+
+
+def step_durations(fn, steps, torch):
+    """Duration of each of `steps` back-to-back calls (microseconds) from events recorded between
+    them on the stream the library launches on; nothing synchronises inside the loop."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    marks[0].record()
+    for i in range(steps):
+        fn()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    return [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(steps)]
 
 
 def kernel_bytes(w, lens, acc):
@@ -152,15 +187,37 @@ def rank_study(inp, w, sched, torch, StepRunner):
     return res
 
 
-def cpu_baseline(inp, w, sched):
-    """Oracle wall time for one step on the host cores.
+def _host_view(inp, layer_pos, b):
+    """Logical (q, K, V) bf16 bit patterns of sequence b on the host, for the oracle (input marshalling only)."""
+    import numpy as np
+    import torch
 
-    One layer of each kind is timed on sequence 0 first; if that projects to at most 30 s the whole
-    step (every layer, every sequence) is run and its measured time reported, otherwise the
-    projection is."""
     import oracle
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import host_view
+    from paper_2508_07101_amd.workloads import bf16_bits
+    lay = inp.layers[layer_pos]
+    L = inp.seq_lens_host[b]
+    q = bf16_bits(lay.q[b])
+    if inp.block_table is None:
+        return q, bf16_bits(lay.k[b, :, :L]), bf16_bits(lay.v[b, :, :L])
+    n = (L + inp.workload.page_size - 1) // inp.workload.page_size
+    bt = inp.block_table[b, :n].cpu().numpy()
+    sel = torch.as_tensor(bt, device=lay.k.device, dtype=torch.long)      # this sequence's pages, in logical order
+    local = np.arange(n, dtype=np.int32)
+    return q, oracle.resolve_paged(bf16_bits(lay.k[sel]), local, L), oracle.resolve_paged(bf16_bits(lay.v[sel]), local, L)
+
+
+def _set_omp_threads(n):
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
+def cpu_baseline(inp, w, sched, single_thread_too=False):
+    """Oracle wall time for one step on the host cores, split by stage.
+
+    One layer of each kind is timed on sequence 0 (full attention, selection = scores + per-head
+    top-k + union + window, sparse attention over the rho just selected).  If that projects to at
+    most 20 s the whole step (every layer, every sequence) is run and its measured time reported,
+    otherwise the projection is (other sequences scaled by length, other layers by count)."""
+    import oracle
 
     def timed(fn):
         t0 = time.perf_counter()
@@ -168,39 +225,188 @@ def cpu_baseline(inp, w, sched):
         return time.perf_counter() - t0, r
 
     sel = sched.index(1)
-    q, K, V = host_view(inp, sel, 0)
+    sp = sched.index(2)
+    q, K, V = _host_view(inp, sel, 0)
+    q2, K2, V2 = _host_view(inp, sp, 0)
     t_full, _ = timed(lambda: oracle.attention(q, K, V))
     t_sel, rho0 = timed(lambda: oracle.select(q, K, w.budget, w.window, w.topk_per_head))
-    sp = sched.index(2)
-    q, K, V = host_view(inp, sp, 0)
-    t_sparse, _ = timed(lambda: oracle.attention(q, K, V, rho0))
+    t_sparse, _ = timed(lambda: oracle.attention(q2, K2, V2, rho0))
+    cores = oracle.num_threads()
     n_full = sum(1 for k in sched if k in (0, 1))
     n_sparse = sum(1 for k in sched if k == 2)
     scale = sum(inp.seq_lens_host) / inp.seq_lens_host[0]          # other sequences, by length
-    projected = (n_full * t_full + t_sel) * scale + n_sparse * t_sparse * w.batch
-    base = {"unit": "us", "cores": oracle.num_threads(), "kind": "oracle"}
-    if projected > 30.0:
-        base.update(value=projected * 1e6,
-                    sample=(f"sequence 0 of {w.batch}: one full-attention layer ({t_full:.3f} s), one selection "
-                            f"({t_sel:.3f} s), one sparse layer ({t_sparse:.4f} s); projected to {n_full} full + 1 select + "
-                            f"{n_sparse} sparse layers and to all sequences by length"))
+    stage = {"full_attention_s": n_full * t_full * scale, "selection_s": t_sel * scale,
+             "sparse_attention_s": n_sparse * t_sparse * w.batch}
+    projected = sum(stage.values())
+    base = {"unit": "us", "cores": cores, "kind": "oracle",
+            "sequence0_one_layer_s": {"full_attention": round(t_full, 4), "selection": round(t_sel, 4),
+                                      "sparse_attention": round(t_sparse, 5), "context": inp.seq_lens_host[0]}}
+    if single_thread_too:
+        _set_omp_threads(1)
+        s_full, _ = timed(lambda: oracle.attention(q, K, V))
+        s_sel, _ = timed(lambda: oracle.select(q, K, w.budget, w.window, w.topk_per_head))
+        s_sparse, _ = timed(lambda: oracle.attention(q2, K2, V2, rho0))
+        _set_omp_threads(cores)
+        base["single_thread_s"] = {"full_attention": round(s_full, 4), "selection": round(s_sel, 4),
+                                   "sparse_attention": round(s_sparse, 5),
+                                   "step": round(n_full * s_full + s_sel + n_sparse * s_sparse, 4)}
+    if projected > 20.0:
+        base.update(value=round(projected * 1e6, 1), stage_seconds={k: round(v, 4) for k, v in stage.items()},
+                    sample=(f"sequence 0 of {w.batch}: one full-attention layer, one selection, one sparse layer; "
+                            f"projected to {n_full} full + 1 select + {n_sparse} sparse layers and to all sequences by length"))
         return base
-    total = 0.0
+    stage = {"full_attention_s": 0.0, "selection_s": 0.0, "sparse_attention_s": 0.0}
     rho = [None] * w.batch
     for i, kind in enumerate(sched):
         for b in range(w.batch):
-            q, K, V = host_view(inp, i, b)                            # device -> host copy, not timed
+            q, K, V = _host_view(inp, i, b)                          # device -> host copy, not timed
             if kind == 2:
                 dt, _ = timed(lambda: oracle.attention(q, K, V, rho[b]))
+                stage["sparse_attention_s"] += dt
             else:
                 dt, _ = timed(lambda: oracle.attention(q, K, V))
+                stage["full_attention_s"] += dt
                 if kind == 1:
                     d2, rho[b] = timed(lambda: oracle.select(q, K, w.budget, w.window, w.topk_per_head))
-                    dt += d2
-            total += dt
-    base.update(value=total * 1e6,
-                sample=f"the whole step: all {len(sched)} layers of all {w.batch} sequences, oracle calls only (host copies of the inputs not timed)")
+                    stage["selection_s"] += d2
+    base.update(value=round(sum(stage.values()) * 1e6, 1), stage_seconds={k: round(v, 4) for k, v in stage.items()},
+                sample=f"the whole step: all {len(sched)} layers of all {w.batch} sequences, oracle calls only "
+                       f"(host copies of the inputs not timed)")
     return base
+
+
+def stream_read_probe(torch, cb):
+    """Read rate of a plain streaming kernel over 4 GiB (far beyond the 256 MB last-level cache)."""
+    n = 1 << 32
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    src.fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for _ in range(2):
+        cb.probe_stream_read(src, sink)
+    torch.cuda.synchronize()
+    cb.profile_reset()
+    cb.profile_enable(True)
+    reps = 10
+    for _ in range(reps):
+        cb.probe_stream_read(src, sink)
+    torch.cuda.synchronize()
+    p = cb.profile_read()["probe_stream_read_kernel"]
+    cb.profile_enable(False)
+    cb.profile_reset()
+    us = p["total_ms"] * 1e3 / p["calls"]
+    del src
+    torch.cuda.empty_cache()
+    gbs = n / (us * 1e-6) / 1e9
+    return {"kernel": "probe_stream_read_kernel", "bytes": n, "avg_us": round(us, 2), "GBs": round(gbs, 1),
+            "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "launches": reps}
+
+
+def measure(name, args, torch, acc, cb, wl, StepRunner):
+    """Everything reported for one workload."""
+    w = wl.WORKLOADS[name]
+    if args.head_overlap is not None:
+        w = wl.scaled(w, lowrank=8, lowrank_scale=args.head_overlap, n_planted=0)
+    inp = wl.make_inputs(w, "cuda:0")
+    sched = list(w.schedule)
+    lens = inp.seq_lens_host
+    r = StepRunner(inp, sched)
+    torch.cuda.synchronize()
+
+    run_step = r.run
+    steps, warmup = args.steps, args.warmup
+    if w.grow_room > 0:
+        if args.graph or 2 * steps + warmup > w.grow_room:
+            raise SystemExit(f"workload {w.name}: at most {w.grow_room} steps (warm-up and both timing passes "
+                             f"included), and no --graph")
+
+        def run_step():                           # one decode step, then the sequences are one token longer
+            r.run()
+            r.grow(1)
+    if args.graph:
+        r.run()                                   # the first call on a device does the library's set-up
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            r.run()
+        run_step = graph.replay
+    step_s = time_steps(run_step, steps, warmup, torch)
+    durs = step_durations(run_step, steps, torch)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    full_s = None
+    if not args.no_full_baseline and w.grow_room == 0:
+        rf = StepRunner(inp, [0] * len(sched))
+        full_s = time_steps(rf.run, max(3, steps // 4), 1, torch)
+        del rf
+
+    kernels, rooflines = {}, []
+    if not args.no_kernel_timing and w.grow_room == 0:
+        cb.profile_reset()
+        cb.profile_enable(True)
+        for _ in range(steps):
+            r.run()
+        torch.cuda.synchronize()
+        prof = cb.profile_read()
+        cb.profile_enable(False)
+        kb = kernel_bytes(w, lens, acc)
+        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
+        counted = json.load(open(tpath)).get("hbm_bytes_per_launch", {}) if os.path.exists(tpath) else {}
+        for kname, p in prof.items():
+            if p["calls"] == 0:
+                continue
+            avg_us = p["total_ms"] * 1e3 / p["calls"]
+            k = {"launches_per_step": p["calls"] // steps, "avg_us": round(avg_us, 3),
+                 "us_per_step": round(p["total_ms"] * 1e3 / steps, 3)}
+            if kname in kb and kb[kname] > 0:
+                k["bytes_per_launch"] = kb[kname]
+                k["achieved_GBs"] = round(kb[kname] / (avg_us * 1e-6) / 1e9, 1)
+                k["frac_of_hbm_peak"] = round(k["achieved_GBs"] / HBM_PEAK_GBS, 4)
+            kernels[kname] = k
+        for kname in BANDWIDTH_KERNELS:
+            if kname in kernels:
+                k = kernels[kname]
+                # traffic: HBM bytes per launch from rocprofv3 counters, where a summary of them is committed
+                rooflines.append({"kernel": kname, "bound": "hbm", "achieved": k["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "frac": k["frac_of_hbm_peak"], "traffic": counted.get(kname),
+                                  "bytes_per_launch": k["bytes_per_launch"], "avg_us": k["avg_us"],
+                                  "us_per_step": k["us_per_step"]})
+
+    sb = acc.step_bytes(sched, lens, w.n_kv_heads, w.budget, w.window)
+    rec = {
+        "us_per_step": {"mean": round(step_s * 1e6, 2), "median": round(statistics.median(durs), 2),
+                        "min": round(min(durs), 2), "steps": steps, "warmup": warmup},
+        "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads}q/{w.n_kv_heads}kv heads, "
+                               f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
+                               f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
+                   "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream",
+                   "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed",
+                   "kv_cache_bytes": int(sum(2 * w.n_kv_heads * L * w.head_dim * 2 for L in lens) *
+                                         (1 if w.same_layer_sparse else w.n_layers)),
+                   **({"head_overlap": args.head_overlap} if args.head_overlap is not None else {})},
+        "step_algorithmic_bytes": sb["total"],
+        "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
+        "rooflines": rooflines,
+        "kernels": kernels,
+    }
+    if full_s is not None:
+        rec["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
+        rec["speedup_vs_full_attention"] = round(full_s / step_s, 3)
+    if not args.no_per_head and 2 in sched and w.grow_room == 0:
+        rec["per_head_comparison"] = per_head_comparison(r, w, sched, lens, max(3, steps // 2), torch, cb, acc)
+    if args.rank_study and 2 in sched:
+        rec["rank_study"] = rank_study(inp, w, sched, torch, StepRunner)
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(inp, w, sched, single_thread_too=(w.name == "c1"))
+    del r, inp
+    torch.cuda.empty_cache()
+    return rec
 
 
 def main():
@@ -218,103 +424,39 @@ def main():
     from paper_2508_07101_amd import workloads as wl
     from paper_2508_07101_amd.runner import StepRunner
 
-    w = wl.WORKLOADS[args.workload]
-    if args.head_overlap is not None:
-        w = wl.scaled(w, lowrank=8, lowrank_scale=args.head_overlap, n_planted=0)
-    inp = wl.make_inputs(w, "cuda:0")
-    sched = list(w.schedule)
-    lens = inp.seq_lens_host
-    r = StepRunner(inp, sched)
-    torch.cuda.synchronize()
-
-    run_step = r.run
-    if w.grow_room > 0:
-        if args.graph or args.steps + args.warmup > w.grow_room:
-            print(f"workload {w.name}: at most {w.grow_room} steps (warm-up included), and no --graph", file=sys.stderr)
-            sys.exit(2)
-
-        def run_step():                           # one decode step, then the sequences are one token longer
-            r.run()
-            r.grow(1)
-    if args.graph:
-        r.run()                                   # warm the library before capture
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            r.run()
-        run_step = graph.replay
-    step_s = time_steps(run_step, args.steps, args.warmup, torch)
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    full_s = None
-    if not args.no_full_baseline:
-        rf = StepRunner(inp, [0] * len(sched))
-        full_s = time_steps(rf.run, max(3, args.steps // 4), 1, torch)
-        del rf
-
-    kernels, roofline = {}, None
-    if not args.no_kernel_timing:
-        cb.profile_reset()
-        cb.profile_enable(True)
-        for _ in range(args.steps):
-            r.run()
-        torch.cuda.synchronize()
-        prof = cb.profile_read()
-        cb.profile_enable(False)
-        kb = kernel_bytes(w, lens, acc)
-        for name, p in prof.items():
-            if p["calls"] == 0:
-                continue
-            avg_us = p["total_ms"] * 1e3 / p["calls"]
-            k = {"launches_per_step": p["calls"] // args.steps, "avg_us": round(avg_us, 3),
-                 "us_per_step": round(p["total_ms"] * 1e3 / args.steps, 3)}
-            if name in kb and kb[name] > 0:
-                k["bytes_per_launch"] = kb[name]
-                k["achieved_GBs"] = round(kb[name] / (avg_us * 1e-6) / 1e9, 1)
-                k["frac_of_hbm_peak"] = round(k["achieved_GBs"] / HBM_PEAK_GBS, 4)
-            kernels[name] = k
-        hot = max((n for n in kernels if "achieved_GBs" in kernels[n]), key=lambda n: kernels[n]["us_per_step"])
-        traffic = None                            # HBM bytes per launch from rocprofv3 counters, if a summary is committed
-        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch", {}).get(hot)
-        roofline = {"kernel": hot, "bound": "hbm", "achieved": kernels[hot]["achieved_GBs"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": kernels[hot]["frac_of_hbm_peak"], "traffic": traffic,
-                    "bytes_per_launch": kernels[hot]["bytes_per_launch"], "avg_us": kernels[hot]["avg_us"]}
-
-    sb = acc.step_bytes(sched, lens, w.n_kv_heads, w.budget, w.window)
+    names = [n for n in args.workloads.split(",") if n]
+    for n in names:
+        if n not in wl.WORKLOADS:
+            raise SystemExit(f"unknown workload {n}: choose from {sorted(wl.WORKLOADS)}")
+    t_start = time.perf_counter()
+    probe = None if args.no_probe else stream_read_probe(torch, cb)
+    configs = {}
+    for n in names:
+        t0 = time.perf_counter()
+        configs[n] = measure(n, args, torch, acc, cb, wl, StepRunner)
+        configs[n]["bench_seconds"] = round(time.perf_counter() - t0, 1)
+        print(f"[bench] {n}: {configs[n]['us_per_step']['mean']} us/step ({configs[n]['bench_seconds']} s)",
+              file=sys.stderr, flush=True)
+    head = configs[names[-1]]
+    # the headline roofline: the bandwidth kernel that takes most of the headline workload's step
+    roofline = max(head["rooflines"], key=lambda k: k["us_per_step"]) if head["rooflines"] else None
     out = {
         "metric": "us_per_decode_step_select_plus_sparse_attn",
-        "value": round(step_s * 1e6, 2), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(step_s * 1e3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads}q/{w.n_kv_heads}kv heads, "
-                               f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
-                               f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
-                   "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream",
-                   "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed",
-                   **({"head_overlap": args.head_overlap} if args.head_overlap is not None else {})},
-        "step_algorithmic_bytes": sb["total"],
-        "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
+        "value": head["us_per_step"]["mean"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["us_per_step"]["mean"] / 1e3, 5), "higher_is_better": False, "scaling": "none (one GPU)",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": head["config"],
+        "step_algorithmic_bytes": head["step_algorithmic_bytes"],
+        "step_achieved_GBs": head["step_achieved_GBs"],
         "roofline": roofline,
-        "kernels": kernels,
+        "cpu_baseline": head.get("cpu_baseline"),
+        "stream_read_probe": probe,
+        "configs": configs,
+        "bench_seconds": round(time.perf_counter() - t_start, 1),
     }
-    if full_s is not None:
-        out["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
-        out["speedup_vs_full_attention"] = round(full_s / step_s, 3)
-    if not args.no_per_head and 2 in sched:
-        out["per_head_comparison"] = per_head_comparison(r, w, sched, lens, max(3, args.steps // 2), torch, cb, acc)
-    if args.rank_study and 2 in sched:
-        out["rank_study"] = rank_study(inp, w, sched, torch, StepRunner)
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inp, w, sched)
+    if "speedup_vs_full_attention" in head:
+        out["full_attention_all_layers_us"] = head["full_attention_all_layers_us"]
+        out["speedup_vs_full_attention"] = head["speedup_vs_full_attention"]
     print(json.dumps(out), flush=True)
 
 

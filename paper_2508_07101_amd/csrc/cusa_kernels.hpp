@@ -1089,6 +1089,12 @@ __device__ __forceinline__ int wave_base_of(unsigned tid) { return (int)(tid >> 
 // LDS written by some lanes of a wave and read by others of the same wave: a wave's LDS
 // accesses are performed in program order, so only the compiler has to be kept from
 // reordering them.
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for
+// its outstanding global loads (which a full __syncthreads() would drain first).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1127,14 +1133,11 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
-    // A wave's softmax numerators take the place of its K rows once those are scored.  Groups of
-    // up to 4 heads keep them in binary32, by token.  A group of 8 is bound by the P.V products on
-    // the VALU and halves them with bf16 pair products (PAIRS): the numerators are stored as bf16,
-    // [pair of row loads j][row group r][head][member], so that the two tokens a lane multiplies
-    // together (rows 2j and 2j+1 of group r) sit in one 32-bit word per head.
-    constexpr bool PAIRS = GQ >= 8;
-    static_assert(TI % 2 == 0 && TILE * 256 >= TILE * SETS * 16, "the numerators must fit the K tile buffer");
-    f32x4(*const pbuf)[SETS] = reinterpret_cast<f32x4(*)[SETS]>(ktile);
+    // A wave's softmax numerators take the place of its K rows once those are scored.  They are
+    // stored as bf16 in the operand order of the P.V products below: [row group r][four row loads ig]
+    // [set][head][member k], so that the weights of one head for the four tokens a lane multiplies
+    // together (rows 4ig .. 4ig+3 of its row group) are one 8-byte word.
+    static_assert(TI % 4 == 0 && TILE * 256 >= TI * SETS * 32, "the numerators must fit the K tile buffer");
     __bf16* const pbuf16 = reinterpret_cast<__bf16*>(ktile);
     // q in LDS: a private bf16 copy per wave, or -- in the scoring variant, whose product chain takes
     // binary32 operands -- one binary32 copy for the workgroup (every wave writes all of it with the
@@ -1142,6 +1145,10 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int QSF = 132;                          // padded head stride of the binary32 copy (floats)
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[SCORE ? 1 : ATTN_WAVES][SCORE ? 8 : SETS * 4 * QSB];
     __shared__ __attribute__((aligned(16))) float qf32[SCORE ? SETS * 4 * QSF : 4];
+    // scoring variant: the workgroup's scores of the last STAGE_IT iterations, [head][token], on their way to P
+    constexpr int STAGE_IT = GQ >= 8 ? 1 : 2;
+    constexpr int STAGE_TOK = STAGE_IT * WG_TILE;
+    __shared__ __attribute__((aligned(16))) float pstage[SCORE ? GQ * STAGE_TOK : 4];
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
@@ -1152,14 +1159,21 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int begin = split * chunk;
     const int32_t* __restrict__ my_idx = idx + (PER_HEAD ? (int64_t)b * G + gy : (int64_t)b) * budget;
     const int64_t head0 = (int64_t)b * H + gy * GQ;      // first query head of this group
-    // The token indices of a tile are fetched one tile ahead, the first ones before the token
-    // count is known: the row of idx has `budget` entries, so a read clamped to budget - 1 stays
-    // inside it, and entries past the count are masked below like every row past the run's end.
-    int pos_next[TI];
-    if (SPARSE) {
+    // Address pipeline.  A row's address is the end of a chain of dependent memory reads: the token
+    // list (sparse), then the block table (paged), then the row.  The list entries (posA) of a tile
+    // are requested one tile ahead, and so are the pool pages (pgA) of a pass over all tokens, whose
+    // positions are arithmetic.  The first entries are fetched here, before the token count is
+    // known: a row of idx has `budget` entries, so a read clamped to budget - 1 stays inside it, and
+    // entries past the count are masked below like every row past the run's end.
+    const int tile0 = begin + wave * TILE;
+    int posA[TI], pgA[TI];
+    auto idx_load = [&](int t_, int* p) {
+        if (SPARSE) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(begin + wave * TILE + i * 4 + r, budget - 1)];
-    }
+            for (int i = 0; i < TI; ++i) p[i] = my_idx[min(t_ + i * 4 + r, budget - 1)];
+        }
+    };
+    idx_load(tile0, posA);
 
     // Every wave keeps its own bf16 copy of q in LDS (no workgroup barrier on the way in): lane l
     // fetches 16 bytes of head l / 16 per set now and parks them once the first tile's loads are
@@ -1181,7 +1195,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     asm volatile("" ::"s"(L), "s"(n), "s"(kv.k), "s"(H));
     if (SPARSE) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) asm volatile("" ::"v"(pos_next[i]));
+        for (int i = 0; i < TI; ++i) asm volatile("" ::"v"(posA[i]));
     }
     if (split > 0 && begin >= n) return;                 // split >= attn_active_splits(n, chunk)
     const int end = (begin + chunk < n) ? begin + chunk : n;
@@ -1191,58 +1205,130 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // heads of each set.  Lane t scores token t % TILE of the tile.
     const int tl = lane % TILE;
     const bool owner = lane < TILE;                   // lanes beyond TILE repeat a token; they add nothing to l
-    // token tl is row (tl / 4) of row group (tl % 4): where its numerators go
-    const int pair_slot = ((tl >> 3) * 4 + (tl & 3)), pair_member = (tl >> 2) & 1;
-    float m[GQ], l[GQ], acc[GQ][8];
+    // token tl is row load (tl / 4) of row group (tl % 4): where its numerators go (bf16 elements)
+    const int p_slot = (((tl & 3) * (TI / 4) + (tl >> 4)) * SETS * 4) * 4 + ((tl >> 2) & 3);
+    float m[GQ], l[GQ];
+    f32x4 acc[SETS][8];                               // [set][column e of the lane's 8]: the four heads of the set
 #pragma unroll
     for (int h = 0; h < GQ; ++h) {
         m[h] = -INFINITY;
         l[h] = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
     }
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[s][e] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     // Rows past the end of the run read some token of the sequence (a valid row) so that all
     // loads are unconditional and issue back to back; their scores are masked below.
     // The next tile's K rows are requested as soon as this tile's are parked in LDS, i.e. before
-    // this tile's arithmetic (not in the scoring variant, whose 64-token tiles leave no registers).
+    // this tile's arithmetic (not in the scoring variant, whose 64-token tiles leave no registers
+    // for it; there the rows are requested at the top of the tile's own iteration).
     constexpr bool PREFETCH = !SCORE;
+    // The scoring variant of a group of 8 has no registers for K and V rows at once (64 each at 64-token
+    // tiles, beside 64 accumulators): its V rows are requested once the K rows are parked in LDS.
+    constexpr bool V_LATE = SCORE && GQ >= 8;
     u32x4 kreg[TI], vreg[TI];
     int64_t off[TI];
-    auto tile_offsets = [&](int t_) {
+    // a valid position for row load i of the tile that starts at list entry t_ (an index outside the
+    // sequence is a caller error; never fault on it)
+    auto tile_pos = [&](int t_, int i, const int* p) {
+        return SPARSE ? min(max(p[i], 0), L - 1) : min(t_ + i * 4 + r, end - 1);
+    };
+    // Pool pages of the tile's rows.  A pass over all tokens walks the table in order: tiles start at
+    // multiples of 16 tokens, so row loads 4ig .. 4ig+3 of every lane fall into one page, entry
+    // (t_ / 16 + ig) of the table (rows clamped to the run's last token: that token's page), and only
+    // TI / 4 wave-uniform entries are fetched.
+    auto page_load = [&](int t_, const int* p, int* g) {
+        if constexpr (PAGED && SPARSE) {
+#pragma unroll
+            for (int i = 0; i < TI; ++i) g[i] = kv.bt[(int64_t)b * kv.max_pages + (tile_pos(t_, i, p) >> 4)];
+        } else if constexpr (PAGED) {
+#pragma unroll
+            for (int ig = 0; ig < TI / 4; ++ig)
+                g[ig * 4] = kv.bt[(int64_t)b * kv.max_pages + min((t_ >> 4) + ig, (end - 1) >> 4)];
+#pragma unroll
+            for (int i = 0; i < TI; ++i) g[i] = g[i & ~3];
+        }
+    };
+    auto make_off = [&](int t_, const int* p, int* g) {
+        if constexpr (SPARSE && PAGED) page_load(t_, p, g);
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
-            // an index outside the sequence is a caller error; never fault on it
-            const int pos = SPARSE ? min(max(pos_next[i], 0), L - 1) : min(t_ + i * 4 + r, end - 1);
-            off[i] = row_offset<PAGED>(kv, b, kvh, pos) + c * 8;
+            const int pos = tile_pos(t_, i, p);
+            if (PAGED) off[i] = (((int64_t)g[i] * kv.G + kvh) * PAGE + (pos & (PAGE - 1))) * D + c * 8;
+            else off[i] = (int64_t)b * kv.sb + (int64_t)kvh * kv.sh + (int64_t)pos * kv.st + c * 8;
         }
     };
     auto request_k = [&]() {
 #pragma unroll
         for (int i = 0; i < TI; ++i) kreg[i] = *reinterpret_cast<const u32x4*>(kv.k + off[i]);
     };
-    auto request_next_idx = [&](int t_) {              // the token indices of the tile that starts at t_
-        if (SPARSE) {
-            __builtin_amdgcn_sched_barrier(0);
+    // After the rows of the tile at t_ have been requested: the lookups for the tile after it.
+    auto advance = [&](int t_) {
+        idx_load(t_ + WG_TILE, posA);
+        if constexpr (!SPARSE) page_load(t_ + WG_TILE, posA, pgA);   // sparse: looked up where the offsets are made
+    };
+    if constexpr (!SPARSE) page_load(tile0, posA, pgA);
+    if (PREFETCH && tile0 < end) {
+        make_off(tile0, posA, pgA);
+        request_k();
+        advance(tile0);
+    }
+    // Scoring variant: the scores go to P through a staging buffer in LDS that the whole workgroup
+    // writes out every STAGE_IT iterations (8 KB at a time).  A few per cent of small writes scattered
+    // through a streaming read cost this machine a sixth of its read rate; the same bytes written in
+    // workgroup-sized bursts cost a third of that (measured with plain read / write kernels).  The
+    // burst is issued before the next tile's rows are requested, while the wave has nothing else
+    // outstanding: issued behind those requests it was measured to cost as much as the scattered
+    // stores (c5: 1030 against 965 us for the pass; 870 us with no stores at all).
+    auto flush_scores = [&](int g0, int n_tok) {       // staged tokens [g0, g0 + n_tok) of this workgroup's run
+        if constexpr (SCORE) {
+            const int lim = min(end, L - window);      // candidates only; L <= budget: rho is every token, nothing is scored
+            if (L > budget && g0 < lim) {
+                const int quads = n_tok >> 2;
+                for (int i = tid; i < GQ * quads; i += ATTN_THREADS) {
+                    const int h = i / quads, w4 = (i - h * quads) * 4, t = g0 + w4;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(&pstage[h * STAGE_TOK + w4]);
+                    float* const dst = &P[(head0 + h) * ldp + t];
+                    if (t + 3 < lim) {
+                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+                    } else {
 #pragma unroll
-            for (int i = 0; i < TI; ++i) pos_next[i] = my_idx[min(t_ + i * 4 + r, budget - 1)];
+                        for (int e = 0; e < 4; ++e)
+                            if (t + e < lim) dst[e] = v[e];
+                    }
+                }
+            }
         }
     };
-    if (PREFETCH && begin + wave * TILE < end) {
-        tile_offsets(begin + wave * TILE);
-        request_k();
-        request_next_idx(begin + wave * TILE + WG_TILE);
-    }
-    for (int t0 = begin + wave * TILE; t0 < end; t0 += WG_TILE) {
+    int it = 0;                                          // iterations of the workgroup so far
+    for (int w0 = begin; w0 < end; w0 += WG_TILE, ++it) {
+        const int t0 = w0 + wave * TILE;
+        // Only the scoring variant has workgroup barriers inside the loop; there a wave whose tile lies
+        // past the run's end still takes part in them.
+        const bool active = t0 < end;
+        const bool burst_due = SCORE && it > 0 && it % STAGE_IT == 0;      // workgroup-uniform
+        if (burst_due) {
+            lds_barrier();                               // every wave's scores of the last STAGE_IT iterations are staged
+            flush_scores(w0 - STAGE_TOK, STAGE_TOK);
+            lds_barrier();                               // ... and read, before the buffer is written again
+        }
+        if (!active) {
+            if constexpr (!SCORE) break;
+            continue;
+        }
         if constexpr (!PREFETCH) {
-            tile_offsets(t0);
+            make_off(t0, posA, pgA);
             // K rows first: they are needed first (parked in LDS and scored), and loads return in
             // order, so the scores are under way while the V rows are still arriving.
             request_k();
         }
+        if constexpr (!V_LATE) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
-        if constexpr (!PREFETCH) request_next_idx(t0 + WG_TILE);
+            for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+        }
+        if constexpr (!PREFETCH) advance(t0);
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         if (!q_parked) {
 #pragma unroll
@@ -1265,10 +1351,15 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             ktile[row * 16 + (c ^ (row & 7))] = kreg[i];
         }
         wave_lds_sync();
+        if constexpr (V_LATE) {
+#pragma unroll
+            for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (PREFETCH && t0 + WG_TILE < end) {
-            tile_offsets(t0 + WG_TILE);
+            make_off(t0 + WG_TILE, posA, pgA);
             request_k();
-            request_next_idx(t0 + 2 * WG_TILE);
+            advance(t0 + WG_TILE);
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -1298,11 +1389,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
                     for (int s = 0; s < SETS; ++s)
                         sc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], sc[s], 0, 0, 0);
             }
-            // L <= budget: rho is every token and nothing is scored
-            const int t = t0 + tl;
-            if (lane < TILE && L > budget && t < L - window && t < end) {
+            if (lane < TILE) {
 #pragma unroll
-                for (int h = 0; h < GQ; ++h) P[(head0 + h) * ldp + t] = sc[h >> 2][h & 3];
+                for (int h = 0; h < GQ; ++h) pstage[h * STAGE_TOK + (it % STAGE_IT) * WG_TILE + wave * TILE + tl] = sc[h >> 2][h & 3];
             }
         } else {
 #pragma unroll
@@ -1331,67 +1420,54 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             const float m_new = fmaxf(m[h], mt);      // finite: token t0 of this tile is valid
             corr[h] = exp2f(m[h] - m_new);
             m[h] = m_new;
-            float pz = exp2f(z - m_new);
-            if constexpr (PAIRS) {
-                // the weight enters numerator and denominator as the same bf16 value
-                const __bf16 pb = (__bf16)pz;
-                pbuf16[(pair_slot * GQ + h) * 2 + pair_member] = pb;
-                pz = (float)pb;
+            // the weight enters numerator and denominator as the same bf16 value
+            const __bf16 pb = (__bf16)exp2f(z - m_new);
+            pbuf16[p_slot + h * 4] = pb;
+            l[h] = l[h] * corr[h] + (owner ? (float)pb : 0.0f);
+        }
+#pragma unroll
+        for (int s = 0; s < SETS; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                f32x4 a = acc[s][e];
+#pragma unroll
+                for (int hh = 0; hh < 4; ++hh)
+                    if (s * 4 + hh < GQ) a[hh] *= corr[s * 4 + hh];
+                acc[s][e] = a;
             }
-            l[h] = l[h] * corr[h] + (owner ? pz : 0.0f);
-            sc[h >> 2][h & 3] = pz;
-        }
-        if constexpr (!PAIRS) {
-#pragma unroll
-            for (int s = 0; s < SETS; ++s) pbuf[tl][s] = sc[s];
-        }
-#pragma unroll
-        for (int h = 0; h < GQ; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] *= corr[h];
         wave_lds_sync();
-        if constexpr (!PAIRS) {
+        // P.V on the matrix cores, four tokens per instruction.  A lane holds columns 8c .. 8c+7 of the
+        // rows i*4 + r; the same column of four of its rows (4ig .. 4ig+3) is gathered into one bf16
+        // quadruple (V_PERM_B32), which is this lane's column of the 4 x 4 B operand; the A operand is
+        // the four tokens' weights of head (lane % 4).  One V_MFMA_F32_4X4X4_16B_BF16 then adds, for the
+        // lane's column, the four tokens' products of four heads to the binary32 accumulator.
 #pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                float vf[8];
-                unpack8(make_uint4(vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w), vf);
-                f32x4 pv[SETS];
+        for (int ig = 0; ig < TI / 4; ++ig) {
+            s16x4 pa[SETS];
 #pragma unroll
-                for (int s = 0; s < SETS; ++s) pv[s] = pbuf[i * 4 + r][s];
+            for (int s = 0; s < SETS; ++s)
+                pa[s] = *reinterpret_cast<const s16x4*>(pbuf16 + (((r * (TI / 4) + ig) * SETS + s) * 4 + (lane & 3)) * 4);
 #pragma unroll
-                for (int h = 0; h < GQ; ++h)
+            for (int w2 = 0; w2 < 4; ++w2) {
+                const uint32_t r0 = vreg[4 * ig][w2], r1 = vreg[4 * ig + 1][w2], r2 = vreg[4 * ig + 2][w2], r3 = vreg[4 * ig + 3][w2];
+                const uint2 lo = make_uint2(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u));
+                const uint2 hi = make_uint2(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u));
+                const s16x4 vlo = __builtin_bit_cast(s16x4, lo), vhi = __builtin_bit_cast(s16x4, hi);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pv[h >> 2][h & 3], vf[e], acc[h][e]);
-            }
-        } else {
-            // P.V two tokens at a time: the rows 2j and 2j+1 of a lane (tokens 8j + r and 8j + 4 + r) are
-            // interleaved column by column into bf16 pairs, the two tokens' weights of a head arrive as one
-            // bf16 pair, and V_DOT2C_F32_BF16 adds both products to the binary32 accumulator.
-#pragma unroll
-            for (int j = 0; j < TI / 2; ++j) {
-                static_assert(!PAIRS || GQ % 4 == 0, "four heads' pairs are read at a time");
-                bf16x2 vp[8];
-#pragma unroll
-                for (int w2 = 0; w2 < 4; ++w2) {
-                    vp[2 * w2] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], 0x05040100u));
-                    vp[2 * w2 + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(vreg[2 * j + 1][w2], vreg[2 * j][w2], 0x07060302u));
+                for (int s = 0; s < SETS; ++s) {
+                    acc[s][2 * w2] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pa[s], vlo, acc[s][2 * w2], 0, 0, 0);
+                    acc[s][2 * w2 + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pa[s], vhi, acc[s][2 * w2 + 1], 0, 0, 0);
                 }
-                bf16x2 pp[GQ];
-                // same element type as the stores above: the compiler may otherwise take the two for unrelated
-                const bf16x8* const src = reinterpret_cast<const bf16x8*>(pbuf16 + (j * 4 + r) * GQ * 2);
-#pragma unroll
-                for (int q4 = 0; q4 < GQ / 4; ++q4) {
-                    const bf16x8 t8 = src[q4];             // four heads' pairs, one 16-byte read
-#pragma unroll
-                    for (int h = 0; h < 4; ++h) pp[q4 * 4 + h] = bf16x2{t8[2 * h], t8[2 * h + 1]};
-                }
-#pragma unroll
-                for (int h = 0; h < GQ; ++h)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_amdgcn_fdot2_f32_bf16(vp[e], pp[h], acc[h][e], false);
             }
         }
         wave_lds_sync();                              // the tile buffers are rewritten next iteration
+    }
+    if constexpr (SCORE) {
+        if (it > 0) {                                  // the iterations staged since the last burst
+            const int rem = (it - 1) % STAGE_IT + 1;
+            lds_barrier();
+            flush_scores(begin + (it - rem) * WG_TILE, rem * WG_TILE);
+        }
     }
     // Merge.  Inside the wave the four row groups are folded with lane swaps: of the N = 8 GQ
     // values of a lane, two folds leave N / 4 complete sums, those with flat index (head * 8 +
@@ -1402,7 +1478,10 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     {
         float y[N / 2], z[N / 4];
 #pragma unroll
-        for (int v = 0; v < N / 2; ++v) y[v] = fold_halves(acc[v >> 3][v & 7], acc[(v + N / 2) >> 3][(v + N / 2) & 7]);
+        for (int v = 0; v < N / 2; ++v) {
+            constexpr int HALF = N / 2;                  // flat index = head * 8 + column
+            y[v] = fold_halves(acc[v >> 5][v & 7][(v >> 3) & 3], acc[(v + HALF) >> 5][(v + HALF) & 7][((v + HALF) >> 3) & 3]);
+        }
 #pragma unroll
         for (int v = 0; v < N / 4; ++v) z[v] = fold_rows(y[v], y[v + N / 4]);
         const int v0 = (r >> 1) * (N / 2) + (r & 1) * (N / 4);
