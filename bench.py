@@ -42,7 +42,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 QUOTED = ["c1", "c2", "c3", "c4", "c5"]
-BANDWIDTH_KERNELS = ("attn_kernel<sparse>", "attn_kernel<full+score>", "attn_kernel<full>")
+BANDWIDTH_KERNELS = ("attn_kernel<sparse>", "attn_kernel<full+score>", "attn_kernel<full>", "score_kernel")
 
 
 def parse():
@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--workloads", "--workload", dest="workloads", default=",".join(QUOTED),
                     help="comma-separated list of c1..c5 and loop (consecutive decode steps, every sequence one "
                          "token longer after each); the last one listed supplies the top-level figures")
+    ap.add_argument("--entry", default="step", choices=["step", "select"],
+                    help="what a timed call is: the whole decode step (cusa_decode_step), or cusa_select on the selection "
+                         "layer alone (the stand-alone scoring kernel + top-k + union; for kernel traces of that path)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into one HIP graph and time its replays (the library only enqueues kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -313,6 +316,11 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
     torch.cuda.synchronize()
 
     run_step = r.run
+    if args.entry == "select":
+        sel_layer = sched.index(1)
+
+        def run_step():
+            r.select(sel_layer)
     steps, warmup = args.steps, args.warmup
     if w.grow_room > 0:
         if args.graph or 2 * steps + warmup > w.grow_room:
@@ -351,7 +359,7 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
         cb.profile_reset()
         cb.profile_enable(True)
         for _ in range(steps):
-            r.run()
+            run_step()
         torch.cuda.synchronize()
         prof = cb.profile_read()
         cb.profile_enable(False)
@@ -386,6 +394,7 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
                                f"d {w.head_dim}, L {min(lens)}..{max(lens)}, budget {w.budget}, window {w.window}, "
                                f"top-k/head {w.k_eff}, {'paged' if w.paged else 'contiguous'} KV",
                    "schedule": "".join("FSs"[k] for k in sched), "launch": "hip_graph" if args.graph else "stream",
+                   "timed_call": "cusa_decode_step" if args.entry == "step" else "cusa_select on the selection layer",
                    "sinks": w.n_sink, "lengths": "grow by one token per step" if w.grow_room > 0 else "fixed",
                    "kv_cache_bytes": int(sum(2 * w.n_kv_heads * L * w.head_dim * 2 for L in lens) *
                                          (1 if w.same_layer_sparse else w.n_layers)),
@@ -395,10 +404,10 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
         "rooflines": rooflines,
         "kernels": kernels,
     }
-    if full_s is not None:
+    if full_s is not None and args.entry == "step":
         rec["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
         rec["speedup_vs_full_attention"] = round(full_s / step_s, 3)
-    if not args.no_per_head and 2 in sched and w.grow_room == 0:
+    if not args.no_per_head and 2 in sched and w.grow_room == 0 and args.entry == "step":
         rec["per_head_comparison"] = per_head_comparison(r, w, sched, lens, max(3, steps // 2), torch, cb, acc)
     if args.rank_study and 2 in sched:
         rec["rank_study"] = rank_study(inp, w, sched, torch, StepRunner)

@@ -157,6 +157,7 @@ constexpr int SCORE_GRID = 512;    // persistent scoring workgroups: 2 per CU on
 constexpr int MAX_SPLITS = 256;
 constexpr int TARGET_WGS = 512;     // two resident workgroups per CU
 constexpr int CHUNK_CAP = 2048;
+static_assert(ATTN_SCORE_CHUNK_CAP <= CHUNK_CAP && ATTN_SCORE_CHUNK_CAP_G8 <= CHUNK_CAP, "the split bound assumes it");
 
 struct AttnPlan {
     int ti;        // row-load instructions per wave iteration (4 or 8)
@@ -170,10 +171,11 @@ struct AttnPlan {
 // Workgroups with long runs (1024 tokens or more) load 8 rows per lane and iteration, which keeps
 // more bytes in flight; short runs are faster with 4 (measured on all five workloads).
 AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
-    (void)g;
     AttnPlan pl;
     int64_t chunk = ((int64_t)n_max * BG + TARGET_WGS - 1) / TARGET_WGS;
-    if (chunk > CHUNK_CAP) chunk = CHUNK_CAP;
+    // the scoring variant keeps the scores of a workgroup's whole run in LDS
+    const int cap = !wide ? CHUNK_CAP : g >= 8 ? ATTN_SCORE_CHUNK_CAP_G8 : ATTN_SCORE_CHUNK_CAP;
+    if (chunk > cap) chunk = cap;
     pl.ti = wide ? (chunk >= 512 ? 16 : 8) : chunk >= 1024 ? 8 : 4;
     const int wg_tile = pl.ti * 4 * ATTN_WAVES;
     chunk = (chunk + wg_tile - 1) / wg_tile * wg_tile;
@@ -189,11 +191,12 @@ AttnPlan plan_attn(int n_max, int BG, int g, bool wide = false) {
 
 // Upper bound of plan_attn(m, BG', g).n_splits over every m <= n_max and BG' >= BG: with the chunk
 // below its cap a token list is cut into at most ceil(TARGET_WGS / BG) pieces, at the cap into
-// ceil(m / CHUNK_CAP).  Monotone in n_max, so a workspace sized for a capacity serves every
+// ceil(m / cap).  Monotone in n_max, so a workspace sized for a capacity serves every
 // shorter bound.
-int max_splits_bound(int n_max, int BG) {
+int max_splits_bound(int n_max, int BG, int g) {
+    const int cap = g >= 8 ? ATTN_SCORE_CHUNK_CAP_G8 : CHUNK_CAP;   // the smallest cap any variant of this group size has
     const int by_wgs = (TARGET_WGS + BG - 1) / BG;
-    const int by_cap = (n_max + CHUNK_CAP - 1) / CHUNK_CAP;
+    const int by_cap = (n_max + cap - 1) / cap;
     const int m = by_wgs > by_cap ? by_wgs : by_cap;
     return m < MAX_SPLITS ? m : MAX_SPLITS;
 }
@@ -214,8 +217,7 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     w.ldp = (lc + 63) / 64 * 64;
     w.k = resolved_k(p);
     if (w.k < 1) w.k = 1;
-    (void)g;
-    w.max_splits = max_splits_bound(max_seq_len > p->budget ? max_seq_len : p->budget, BG);
+    w.max_splits = max_splits_bound(max_seq_len > p->budget ? max_seq_len : p->budget, BG, g);
     size_t off = 0;
     w.scores = off;    off += align256((size_t)(B * H * w.ldp) * 4);
     w.rho_head = off;  off += align256((size_t)(B * w.k * H) * 4);

@@ -1046,6 +1046,10 @@ __device__ __forceinline__ float row_sum16(float v) {
 
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_WAVES = 4;
+// Longest run of tokens a workgroup of the scoring variant may own: its scores wait in LDS (32 KB)
+// until the run is done.
+constexpr int ATTN_SCORE_CHUNK_CAP = 2048;
+constexpr int ATTN_SCORE_CHUNK_CAP_G8 = 1024;
 
 // Workgroup `split` of a (sequence, KV head) owns tokens [split*chunk, split*chunk + chunk) of
 // the token list; a list of n tokens keeps ceil(n / chunk) workgroups busy (at least one) and
@@ -1128,16 +1132,22 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int QSB = 136;                          // padded head stride of q in LDS (bf16 elements)
     // A wave's K tile buffer (TILE rows of 256 bytes) also carries its partial accumulators
     // (GQ x 128 floats) into the final merge.
-    static_assert(TILE * 256 >= GQ * D * 4, "the K tile buffer must hold a wave's partial accumulators");
-    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[ATTN_WAVES * TILE * 256];
-    u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * 16);   // this wave's K rows, chunk c of row r at slot c ^ (r & 7)
+    // The scoring variant parks a tile's K rows in two halves of 64 columns, one after the other (its
+    // product chain walks the columns in order anyway), which leaves LDS for the scores of the
+    // workgroup's whole run (pstage below).
+    constexpr int KSLOTS = SCORE ? 8 : 16;            // 16-byte slots of a K row held in LDS at a time
+    constexpr int WAVE_LDS = TILE * KSLOTS * 16;      // bytes of a wave's tile buffer
+    static_assert(WAVE_LDS >= GQ * D * 4, "the K tile buffer must hold a wave's partial accumulators");
+    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[ATTN_WAVES * WAVE_LDS];
+    // this wave's K rows: chunk c of row r at slot c ^ (r & 7); scoring variant: chunk c (of the half) at slot c ^ ((r >> 1) & 7)
+    u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * KSLOTS);
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
     // A wave's softmax numerators take the place of its K rows once those are scored.  They are
     // stored as bf16 in the operand order of the P.V products below: [row group r][four row loads ig]
     // [set][head][member k], so that the weights of one head for the four tokens a lane multiplies
     // together (rows 4ig .. 4ig+3 of its row group) are one 8-byte word.
-    static_assert(TI % 4 == 0 && TILE * 256 >= TI * SETS * 32, "the numerators must fit the K tile buffer");
+    static_assert(TI % 4 == 0 && WAVE_LDS >= TI * SETS * 32, "the numerators must fit the K tile buffer");
     __bf16* const pbuf16 = reinterpret_cast<__bf16*>(ktile);
     // q in LDS: a private bf16 copy per wave, or -- in the scoring variant, whose product chain takes
     // binary32 operands -- one binary32 copy for the workgroup (every wave writes all of it with the
@@ -1145,9 +1155,10 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int QSF = 132;                          // padded head stride of the binary32 copy (floats)
     __shared__ __attribute__((aligned(16))) uint16_t qlds_all[SCORE ? 1 : ATTN_WAVES][SCORE ? 8 : SETS * 4 * QSB];
     __shared__ __attribute__((aligned(16))) float qf32[SCORE ? SETS * 4 * QSF : 4];
-    // scoring variant: the workgroup's scores of the last STAGE_IT iterations, [head][token], on their way to P
-    constexpr int STAGE_IT = GQ >= 8 ? 1 : 2;
-    constexpr int STAGE_TOK = STAGE_IT * WG_TILE;
+    // scoring variant: the scores of the workgroup's run (of its last STAGE_IT iterations, should a run be
+    // longer: the host caps it at STAGE_TOK tokens), [head][token], on their way to P
+    constexpr int STAGE_TOK = GQ >= 8 ? ATTN_SCORE_CHUNK_CAP_G8 : ATTN_SCORE_CHUNK_CAP;   // 32 KB at groups of 4 and 8
+    constexpr int STAGE_IT = STAGE_TOK / WG_TILE;
     __shared__ __attribute__((aligned(16))) float pstage[SCORE ? GQ * STAGE_TOK : 4];
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
@@ -1238,7 +1249,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // Pool pages of the tile's rows.  A pass over all tokens walks the table in order: tiles start at
     // multiples of 16 tokens, so row loads 4ig .. 4ig+3 of every lane fall into one page, entry
     // (t_ / 16 + ig) of the table (rows clamped to the run's last token: that token's page), and only
-    // TI / 4 wave-uniform entries are fetched.
+    // TI / 4 wave-uniform entries are fetched (g[ig]).
     auto page_load = [&](int t_, const int* p, int* g) {
         if constexpr (PAGED && SPARSE) {
 #pragma unroll
@@ -1246,9 +1257,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         } else if constexpr (PAGED) {
 #pragma unroll
             for (int ig = 0; ig < TI / 4; ++ig)
-                g[ig * 4] = kv.bt[(int64_t)b * kv.max_pages + min((t_ >> 4) + ig, (end - 1) >> 4)];
-#pragma unroll
-            for (int i = 0; i < TI; ++i) g[i] = g[i & ~3];
+                g[ig] = kv.bt[(int64_t)b * kv.max_pages + min((t_ >> 4) + ig, (end - 1) >> 4)];
         }
     };
     auto make_off = [&](int t_, const int* p, int* g) {
@@ -1256,7 +1265,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
 #pragma unroll
         for (int i = 0; i < TI; ++i) {
             const int pos = tile_pos(t_, i, p);
-            if (PAGED) off[i] = (((int64_t)g[i] * kv.G + kvh) * PAGE + (pos & (PAGE - 1))) * D + c * 8;
+            if (PAGED) off[i] = (((int64_t)g[SPARSE ? i : i >> 2] * kv.G + kvh) * PAGE + (pos & (PAGE - 1))) * D + c * 8;
             else off[i] = (int64_t)b * kv.sb + (int64_t)kvh * kv.sh + (int64_t)pos * kv.st + c * 8;
         }
     };
@@ -1276,12 +1285,14 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         advance(tile0);
     }
     // Scoring variant: the scores go to P through a staging buffer in LDS that the whole workgroup
-    // writes out every STAGE_IT iterations (8 KB at a time).  A few per cent of small writes scattered
+    // writes out in one burst.  A few per cent of small writes scattered
     // through a streaming read cost this machine a sixth of its read rate; the same bytes written in
     // workgroup-sized bursts cost a third of that (measured with plain read / write kernels).  The
-    // burst is issued before the next tile's rows are requested, while the wave has nothing else
-    // outstanding: issued behind those requests it was measured to cost as much as the scattered
-    // stores (c5: 1030 against 965 us for the pass; 870 us with no stores at all).
+    // burst is issued at the end of the workgroup's run (the host caps a run at STAGE_TOK tokens; a
+    // longer one would take a burst every STAGE_IT iterations, before the next tile's rows are
+    // requested).  Measured on the selection pass, us without stores / scattered stores / bursts:
+    // c3 95 / 106 / 99, c4 100 / 121 / 106, c5 867 / 1036 / 1008.  Giving every workgroup its own
+    // burst phase, so that the chip's bursts do not coincide, was measured too and is slower.
     auto flush_scores = [&](int g0, int n_tok) {       // staged tokens [g0, g0 + n_tok) of this workgroup's run
         if constexpr (SCORE) {
             const int lim = min(end, L - window);      // candidates only; L <= budget: rho is every token, nothing is scored
@@ -1302,17 +1313,21 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             }
         }
     };
+    int t_opaque = 0;                                    // always zero, unknown to the compiler
+    int it_staged = 0;                                   // first iteration whose scores are still in the staging buffer
     int it = 0;                                          // iterations of the workgroup so far
     for (int w0 = begin; w0 < end; w0 += WG_TILE, ++it) {
         const int t0 = w0 + wave * TILE;
         // Only the scoring variant has workgroup barriers inside the loop; there a wave whose tile lies
         // past the run's end still takes part in them.
         const bool active = t0 < end;
-        const bool burst_due = SCORE && it > 0 && it % STAGE_IT == 0;      // workgroup-uniform
+        // workgroup-uniform; the buffer holds STAGE_IT iterations at most
+        const bool burst_due = SCORE && it - it_staged == STAGE_IT;
         if (burst_due) {
-            lds_barrier();                               // every wave's scores of the last STAGE_IT iterations are staged
-            flush_scores(w0 - STAGE_TOK, STAGE_TOK);
+            lds_barrier();                               // every wave's scores since the last burst are staged
+            flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
             lds_barrier();                               // ... and read, before the buffer is written again
+            it_staged = it;
         }
         if (!active) {
             if constexpr (!SCORE) break;
@@ -1328,7 +1343,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
 #pragma unroll
             for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
         }
-        if constexpr (!PREFETCH) advance(t0);
+        if constexpr (!PREFETCH && !V_LATE) advance(t0);
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
         if (!q_parked) {
 #pragma unroll
@@ -1345,16 +1360,13 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             }
             q_parked = true;
         }
+        if constexpr (!SCORE) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) {
-            const int row = i * 4 + r;
-            ktile[row * 16 + (c ^ (row & 7))] = kreg[i];
-        }
-        wave_lds_sync();
-        if constexpr (V_LATE) {
-#pragma unroll
-            for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < TI; ++i) {
+                const int row = i * 4 + r;
+                ktile[row * 16 + (c ^ (row & 7))] = kreg[i];
+            }
+            wave_lds_sync();
         }
         if (PREFETCH && t0 + WG_TILE < end) {
             make_off(t0 + WG_TILE, posA, pgA);
@@ -1367,31 +1379,58 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
 #pragma unroll
         for (int s = 0; s < SETS; ++s) sc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if constexpr (SCORE) {
+            // columns 0..63, then 64..127: the lanes holding that half of a row park it, every lane then
+            // walks its own token's 64 columns in order
 #pragma unroll
-            for (int cc = 0; cc < 16; ++cc) {
-                const u32x4 kw = ktile[tl * 16 + (cc ^ (tl & 7))];
-                float kf[8];
-                unpack8(make_uint4(kw.x, kw.y, kw.z, kw.w), kf);
-                float qf[SETS][8];
+            for (int half = 0; half < 2; ++half) {
+                if (half) wave_lds_sync();            // the first half has been read
+                if ((c >> 3) == half) {
 #pragma unroll
-                for (int s = 0; s < SETS; ++s) {
-                    const float* const src = &qf32[(s * 4 + (lane & 3)) * QSF + cc * 8];
-                    const f32x4 qa = *reinterpret_cast<const f32x4*>(src), qb = *reinterpret_cast<const f32x4*>(src + 4);
+                    for (int i = 0; i < TI; ++i) {
+                        const int row = i * 4 + r;
+                        ktile[row * 8 + ((c & 7) ^ ((row >> 1) & 7))] = kreg[i];
+                    }
+                }
+                wave_lds_sync();
+                if constexpr (V_LATE) {
+                    if (half) {                       // the K rows' registers are free now
+                        // the offsets are made again rather than kept in 32 registers since the K requests;
+                        // the compiler must not see that they are the same values, or it keeps them
+                        asm volatile("" : "+v"(t_opaque));
+                        make_off(t0 + t_opaque, posA, pgA);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        qf[s][e] = qa[e];
-                        qf[s][4 + e] = qb[e];
+                        for (int i = 0; i < TI; ++i) vreg[i] = *reinterpret_cast<const u32x4*>(kv.v + off[i]);
+                        advance(t0);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
+                for (int c8 = 0; c8 < 8; ++c8) {
+                    const int cc = half * 8 + c8;
+                    const u32x4 kw = ktile[tl * 8 + (c8 ^ ((tl >> 1) & 7))];
+                    float kf[8];
+                    unpack8(make_uint4(kw.x, kw.y, kw.z, kw.w), kf);
+                    float qf[SETS][8];
 #pragma unroll
-                    for (int s = 0; s < SETS; ++s)
-                        sc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], sc[s], 0, 0, 0);
+                    for (int s = 0; s < SETS; ++s) {
+                        const float* const src = &qf32[(s * 4 + (lane & 3)) * QSF + cc * 8];
+                        const f32x4 qa = *reinterpret_cast<const f32x4*>(src), qb = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            qf[s][e] = qa[e];
+                            qf[s][4 + e] = qb[e];
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+#pragma unroll
+                        for (int s = 0; s < SETS; ++s)
+                            sc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], sc[s], 0, 0, 0);
+                }
             }
             if (lane < TILE) {
 #pragma unroll
-                for (int h = 0; h < GQ; ++h) pstage[h * STAGE_TOK + (it % STAGE_IT) * WG_TILE + wave * TILE + tl] = sc[h >> 2][h & 3];
+                for (int h = 0; h < GQ; ++h) pstage[h * STAGE_TOK + (it - it_staged) * WG_TILE + wave * TILE + tl] = sc[h >> 2][h & 3];
             }
         } else {
 #pragma unroll
@@ -1463,10 +1502,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         wave_lds_sync();                              // the tile buffers are rewritten next iteration
     }
     if constexpr (SCORE) {
-        if (it > 0) {                                  // the iterations staged since the last burst
-            const int rem = (it - 1) % STAGE_IT + 1;
+        if (it > it_staged) {                          // the iterations staged since the last burst
             lds_barrier();
-            flush_scores(begin + (it - rem) * WG_TILE, rem * WG_TILE);
+            flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
         }
     }
     // Merge.  Inside the wave the four row groups are folded with lane swaps: of the N = 8 GQ
@@ -1518,7 +1556,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         for (int wv = 0; wv < ATTN_WAVES; ++wv) {
             const float mw = sm_m[wv][h];
             const float f = (mw == -INFINITY) ? 0.0f : exp2f(mw - M);
-            A = __builtin_fmaf(sums[wv * (TILE * 64) + o], f, A);
+            A = __builtin_fmaf(sums[wv * (WAVE_LDS / 4) + o], f, A);
             Ls = __builtin_fmaf(sm_l[wv][h], f, Ls);
         }
         if (n <= chunk) {                                // this workgroup saw the whole token list

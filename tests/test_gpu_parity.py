@@ -507,6 +507,29 @@ def test_planted_heavy_keys_are_selected_on_gpu():
         assert set(planted[b]) <= set(idx[b])
 
 
+def test_decode_step_with_different_length_bounds_per_layer():
+    """Layers of one step may carry different host-side bounds max_seq_len (here 4096 / 4097 / 4096 around a
+    place where the attention kernels' tiling changes); the workspace is sized once, for the largest."""
+    w = small("bounds", n_layers=3, schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE), batch=1, seq_len=4097,
+              lengths=(4090,), budget=512, window=128)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    bounds = [4096, 4097, 4096]
+    kvs = [cb.KvCache(l.k, l.v, inp.seq_lens, m, None) for l, m in zip(inp.layers, bounds)]
+    ws = cb.alloc_workspace(r.params, max(bounds), DEV)
+    assert cb.workspace_bytes(r.params, 4096) <= cb.workspace_bytes(r.params, 4097)
+    cb.decode_step(r.params, list(w.schedule), [l.q for l in inp.layers], kvs, r.outs, r.idx, r.cnt, ws)
+    torch.cuda.synchronize()
+    r.ws, r.max_len = ws, max(bounds)                    # where check_select reads the intermediates from
+    check_select(inp, r, 1)
+    for i, kind in enumerate(w.schedule):
+        check_attention(inp, r, i, kind)
+    # and the other way round: a workspace sized for a capacity serves a shorter bound
+    ws_big = cb.alloc_workspace(r.params, 65536, DEV)
+    cb.full_attn(r.params, inp.layers[0].q, kvs[0], r.outs[0], ws_big)
+    check_attention(inp, r, 0, LAYER_FULL)
+
+
 # ------------------------------------------------------------------ the five workloads at full size
 
 def test_c1_full_size():
@@ -525,12 +548,15 @@ def test_c2_full_size_whole_step_sampled_layers():
         check_attention(inp, r, i, sched[i])
 
 
-def test_c3_full_size_layer_subset_sampled_sequences():
+def test_c3_full_size_every_sequence_selected_layers():
+    """c3 at full size: two full layers, the selection layer, the first and the LAST sparse layer (35).  The
+    selection (scores, ranked lists, idx, cnt) is compared with the oracle for every sequence; attention on
+    two sequences per layer."""
     w = wl.WORKLOADS["c3"]
-    layers = [0, 2, 3]
-    inp, r, sched = run_and_check(w, layers, seqs=[0, 5])
+    layers = [0, 2, 3, 35]
+    inp, r, sched = run_and_check(w, layers)             # seqs=None: all eight sequences
     for i, kind in enumerate(sched):
-        check_attention(inp, r, i, kind, seqs=[5])
+        check_attention(inp, r, i, kind, seqs=[0, 5])
 
 
 def test_c4_full_size():
@@ -539,17 +565,22 @@ def test_c4_full_size():
         check_attention(inp, r, i, kind)
 
 
-def test_c5_full_size_layer_subset_sampled_sequences():
+def test_c5_full_size_whole_step_every_sequence():
+    """c5 at full size, the whole four-layer step as the bench runs it.  The selection is compared with the
+    oracle for every one of the 64 sequences; attention on sampled sequences: the selection layer's own output
+    and the first and last sparse layers."""
     w = wl.WORKLOADS["c5"]
-    inp = wl.make_inputs(w, DEV, layers=[0, 1])
+    inp = wl.make_inputs(w, DEV)
     lens = inp.seq_lens_host
     seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 17})
-    r = StepRunner(inp, [LAYER_SELECT, LAYER_SPARSE])
-    _say(f"c5: 2 layers, sampled sequences {seqs}")
+    r = StepRunner(inp)
+    _say(f"c5: whole step, {len(inp.layers)} layers; attention on sequences {seqs}")
     r.run()
-    check_select(inp, r, 0, seqs)
+    check_select(inp, r, 0)                              # every sequence
+    _say("c5: selection equal to the oracle's for all sequences")
     check_attention(inp, r, 0, LAYER_FULL, seqs[:1])
     check_attention(inp, r, 1, LAYER_SPARSE, seqs)
+    check_attention(inp, r, 3, LAYER_SPARSE, seqs)
     # properties that hold for every sequence, checked without the oracle
     torch.cuda.synchronize()
     idx, cnt = r.idx.cpu().numpy(), r.cnt.cpu().numpy()
