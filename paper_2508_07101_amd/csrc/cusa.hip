@@ -19,11 +19,12 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
-                                             "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel"};
+                                             "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel", "topk_kernel<slice>",
+                                             "topk_kernel<merge>"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -201,8 +202,20 @@ int max_splits_bound(int n_max, int BG, int g) {
     return m < MAX_SPLITS ? m : MAX_SPLITS;
 }
 
+// Slices a row of up to lc_max candidates is cut into: only few long rows are cut (more rows than
+// CUs keep every CU busy anyway), into pieces of about 32768 candidates that a workgroup holds in
+// registers, and only as far as the merge can hold the slices' picks in registers (16384 composites).
+int plan_topk_slices(int64_t rows, int lc_max, int k) {
+    if (lc_max <= 32768 || k < 1) return 1;
+    int64_t s = ((int64_t)lc_max + 32767) / 32768;
+    if (s > 8) s = 8;
+    if (s > 16384 / k) s = 16384 / k;
+    if (s > 512 / rows) s = 512 / rows;
+    return s < 1 ? 1 : (int)s;
+}
+
 struct WsLayout {
-    size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, lse, out_tmp, total;
+    size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, lse, out_tmp, topk_parts, total;
     int64_t ldp;
     int k;
     int max_splits;
@@ -227,6 +240,18 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
     if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE) {   // per-position ranking keys and the unified ranked list
         w.agg = off;       off += align256((size_t)(B * 2 * w.ldp) * 4);
         w.rho_rank = off;  off += align256((size_t)(B * (p->budget - p->window + 1)) * 4);
+    }
+    {   // per-head top-k of few long rows: room for the slices' picks (none when rows are not cut)
+        const int lc_i = (int)(lc > 0x7fffffff ? 0x7fffffff : lc);
+        const int s1 = plan_topk_slices(B * H, lc_i, w.k);
+        size_t n = s1 > 1 ? (size_t)s1 * B * H * w.k : 0;
+        const int n_hist = p->budget - p->window - p->n_sink;
+        if (p->rank_mode != CUSA_RANK_FIRST_OCCURRENCE && n_hist > 0) {   // one key row per sequence is ranked too
+            const int s2 = plan_topk_slices(B, lc_i, n_hist);
+            if (s2 > 1 && (size_t)s2 * B * n_hist > n) n = (size_t)s2 * B * n_hist;
+        }
+        w.topk_parts = off;
+        off += align256(n * 8);
     }
     w.lse = off;      off += align256((size_t)(B * H * 2) * 4);        // recall: denominators over the set and over all tokens
     w.out_tmp = off;  off += align256((size_t)(B * H * D) * 2);        // recall: the attention outputs nobody reads
@@ -413,12 +438,12 @@ bool grant_lds(const void* fn, size_t bytes) {
     return true;
 }
 
-template <int ITEMS>
+template <int ITEMS, bool MERGE = false>
 bool grant_topk_items() {
-    return grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 1>), topk_lds_bytes<ITEMS, 1>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 2>), topk_lds_bytes<ITEMS, 2>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 4>), topk_lds_bytes<ITEMS, 4>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8>), topk_lds_bytes<ITEMS, 8>());
+    return grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 1, MERGE>), topk_lds_bytes<ITEMS, 1>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 2, MERGE>), topk_lds_bytes<ITEMS, 2>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 4, MERGE>), topk_lds_bytes<ITEMS, 4>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8, MERGE>), topk_lds_bytes<ITEMS, 8>());
 }
 
 // Split-K partials of cusa_sparse_attn_noalloc: device memory that belongs to the library image,
@@ -442,7 +467,8 @@ bool device_ready() {
     std::lock_guard<std::mutex> lk(mu);
     if (ready[dev]) return true;
     const bool ok = grant_topk_items<4>() && grant_topk_items<8>() && grant_topk_items<16>() && grant_topk_items<32>() &&
-                    grant_topk_items<0>() && grant_lds(reinterpret_cast<const void*>(union_kernel), SEL_LDS_MAX) &&
+                    grant_topk_items<0>() && grant_topk_items<-1>() && grant_topk_items<4, true>() &&
+                    grant_topk_items<8, true>() && grant_topk_items<16, true>() && grant_lds(reinterpret_cast<const void*>(union_kernel), SEL_LDS_MAX) &&
                     grant_lds(reinterpret_cast<const void*>(per_head_rho_kernel), SEL_LDS_MAX);
     void* ptr = nullptr;
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
@@ -454,36 +480,68 @@ bool device_ready() {
     return ok;
 }
 
-template <int ITEMS, int MTOP>
-cusa_status launch_topk_m(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                          int32_t* rho_head, int H, int k, int budget, int window, int raw, int n_sink) {
+// Arguments of one per-head top-k pass.  parts == nullptr: whole rows, ranked output.  Otherwise the
+// rows are cut into n_slices slices of slice_len positions (grid.z) that leave their k best in parts,
+// and a merge launch ranks among those.
+struct TopkArgs {
+    dim3 grid;
+    hipStream_t s;
+    const float* P;
+    int64_t ldp;
+    const int32_t* seq_lens;
+    int32_t* rho_head;
+    int H, k, budget, window, raw, n_sink;
+    uint64_t* parts;
+    int slice_len, n_slices;
+};
+
+template <int ITEMS, int MTOP, bool MERGE>
+cusa_status launch_topk_m(const TopkArgs& a) {
     const size_t shmem = topk_lds_bytes<ITEMS, MTOP>();
-    launch(KID_TOPK, topk_kernel<ITEMS, MTOP>, grid, SEL_THREADS, shmem, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
+    launch(MERGE ? KID_TOPK_MERGE : a.parts ? KID_TOPK_SLICE : KID_TOPK, topk_kernel<ITEMS, MTOP, MERGE>, a.grid, SEL_THREADS, shmem, a.s, a.P, a.ldp, a.seq_lens, a.rho_head, a.H, a.k,
+           a.budget, a.window, a.raw, a.n_sink, a.parts, a.slice_len, a.n_slices);
     return launch_status();
 }
 
 // MTOP: composites sorted per thread (MTOP * 1024 >= k), also the number of per-thread
 // candidates kept for the lower bound.
-template <int ITEMS>
-cusa_status launch_topk(dim3 grid, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                        int32_t* rho_head, int H, int k, int budget, int window, int raw, int n_sink) {
-    if (k <= 1024) return launch_topk_m<ITEMS, 1>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
-    if (k <= 2048) return launch_topk_m<ITEMS, 2>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
-    if (k <= 4096) return launch_topk_m<ITEMS, 4>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
-    return launch_topk_m<ITEMS, 8>(grid, s, P, ldp, seq_lens, rho_head, H, k, budget, window, raw, n_sink);
+template <int ITEMS, bool MERGE = false>
+cusa_status launch_topk(const TopkArgs& a) {
+    if (a.k <= 1024) return launch_topk_m<ITEMS, 1, MERGE>(a);
+    if (a.k <= 2048) return launch_topk_m<ITEMS, 2, MERGE>(a);
+    if (a.k <= 4096) return launch_topk_m<ITEMS, 4, MERGE>(a);
+    return launch_topk_m<ITEMS, 8, MERGE>(a);
 }
 
 // Ranked top-k of every row of P: rows (b, h) of length L_b - W, output rank-major out[b][j][h].
-// raw: the rows hold uint32 keys instead of scores.
+// raw: the rows hold uint32 keys instead of scores.  parts: room for rows * slices * k composites.
 cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                     int32_t* out, int k, int budget, int window, int raw, int n_sink) {
-    const int items = (lc_max + SEL_THREADS - 1) / SEL_THREADS;
-    const dim3 tg(H, B);
-    if (items <= 4) return launch_topk<4>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
-    if (items <= 8) return launch_topk<8>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
-    if (items <= 16) return launch_topk<16>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
-    if (items <= 32) return launch_topk<32>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
-    return launch_topk<0>(tg, s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink);
+                     int32_t* out, int k, int budget, int window, int raw, int n_sink, uint64_t* parts) {
+    TopkArgs a = {dim3(H, B), s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink, nullptr, 0, 1};
+    const int n_slices = plan_topk_slices((int64_t)B * H, lc_max, k);
+    int n_cand = lc_max;                                  // candidates a workgroup walks
+    if (n_slices > 1) {
+        a.parts = parts;
+        a.n_slices = n_slices;
+        a.slice_len = ((lc_max + n_slices - 1) / n_slices + 4095) / 4096 * 4096;
+        a.grid = dim3(H, B, n_slices);
+        n_cand = a.slice_len;
+    }
+    const int items = (n_cand + SEL_THREADS - 1) / SEL_THREADS;
+    cusa_status st;
+    // many more rows than CUs: the lean streamed kernel, two rows at a time per CU
+    if ((int64_t)B * H >= 512 && items > 8) st = launch_topk<-1>(a);
+    else if (items <= 4) st = launch_topk<4>(a);
+    else if (items <= 8) st = launch_topk<8>(a);
+    else if (items <= 16) st = launch_topk<16>(a);
+    else if (items <= 32) st = launch_topk<32>(a);
+    else st = launch_topk<0>(a);
+    if (st != CUSA_OK || n_slices == 1) return st;
+    a.grid = dim3(H, B);
+    const int m_items = (n_slices * k + SEL_THREADS - 1) / SEL_THREADS;   // <= 16 by the plan
+    if (m_items <= 4) return launch_topk<4, true>(a);
+    if (m_items <= 8) return launch_topk<8, true>(a);
+    return launch_topk<16, true>(a);
 }
 
 template <int GQ>
@@ -525,7 +583,8 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
             }
             if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
         }
-        cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0, p->n_sink);
+        cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0, p->n_sink,
+                                  ws_ptr<uint64_t>(ws, w.topk_parts));
         if (st != CUSA_OK) return st;
     }
     {
@@ -543,7 +602,7 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
                        H, w.k, p->budget, p->window, p->rank_mode == CUSA_RANK_MAX_SCORE ? 1 : 0, p->n_sink);
                 if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
                 const cusa_status st = run_topk(lc_max, B, 1, s, reinterpret_cast<const float*>(agg), 2 * w.ldp, kv->seq_lens,
-                                                rho_rank, n_hist, p->budget, p->window, 1, p->n_sink);
+                                                rho_rank, n_hist, p->budget, p->window, 1, p->n_sink, ws_ptr<uint64_t>(ws, w.topk_parts));
                 if (st != CUSA_OK) return st;
             }
             launch(KID_RHO_PER_HEAD, per_head_rho_kernel, dim3(1, B), SEL_THREADS, bitmap, s, rho_rank, kv->seq_lens, idx, cnt, 1,

@@ -278,7 +278,7 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 //   3. the k survivors are compacted into LDS and bitonic-sorted (descending);
 //   4. ranks are written rank-major: rho_head[b][j][h].
 // With ITEMS > 0 a thread keeps its ITEMS candidates (positions i*1024 + tid) in
-// registers, loaded once with independent loads; ITEMS == 0 re-reads the scores from
+// registers, loaded once with independent loads; ITEMS <= 0 (streamed) re-reads the scores from
 // memory in every pass, 32 independent loads at a time (any length).
 
 struct SelectState {
@@ -379,7 +379,7 @@ __device__ __forceinline__ int wave_reserve(int mine, int* counter) {
 // Entries of the LDS candidate list of topk_kernel<ITEMS, MTOP> (0: no list; short rows are
 // cheap to walk again).
 __host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
-    return (items != 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
+    return (items > 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
 }
 
 // Value of lane (l ^ STRIDE) for STRIDE < 64 without the LDS crossbar: DPP moves inside a 16-lane
@@ -418,11 +418,22 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
     }
 }
 
-template <int ITEMS, int MTOP>
-__global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restrict__ P, int64_t ldp,
+// ITEMS == -1 is the streamed kernel in a register-lean form (half the keys in flight, compiled for two
+// resident workgroups per CU): with many more rows than CUs two rows overlap on a CU, which gains more
+// than the shorter batches lose (c5, 2048 rows: 198 -> 147 us); with one row per CU it is twice as
+// slow as the wide form (c4: 65 -> 134 us), so few long rows keep ITEMS == 0.
+//
+// Few long rows (fewer rows than CUs, more than 32768 candidates) are cut into slices, one workgroup
+// each (blockIdx.z): a slice selects its own k best and leaves their composites, unsorted and padded
+// with zeros, in parts[row][slice][k]; the k best of a row are among the k best of its slices, so a
+// second launch (MERGE) selects and ranks among those n_slices * k composites instead of the row.
+template <int ITEMS, int MTOP, bool MERGE = false>
+__global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
-                                                            int budget, int window, int raw_keys, int n_sink) {
+                                                            int budget, int window, int raw_keys, int n_sink,
+                                                            uint64_t* __restrict__ parts, int slice_len, int n_slices) {
+    static_assert(!MERGE || ITEMS > 0, "the composites of a merge are held in registers");
     constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
     constexpr int CAP = topk_list_cap(ITEMS, MTOP);
     extern __shared__ uint64_t sort_buf[];            // NSORT composites (aliases the histogram), then CAP list entries
@@ -436,27 +447,48 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     const int L = seq_lens[b];
     if (L <= budget) return;
     const int Lc = L - window;
+    // this workgroup's candidates: the positions [t_lo, t_hi) of the row (a slice of it), or -- MERGE --
+    // the composites the slices left
+    const bool slice = !MERGE && parts != nullptr;
+    const int t_lo = slice ? (int)blockIdx.z * slice_len : 0;
+    const int t_hi = slice ? min(Lc, t_lo + slice_len) : Lc;
+    uint64_t* const my_parts = parts + (((int64_t)b * H + h) * n_slices + (slice ? (int)blockIdx.z : 0)) * k;
     // the first n_sink positions are kept in rho anyway and are no candidates (key 0, like the padding)
-    const int k_eff = k < Lc - n_sink ? k : Lc - n_sink;
+    const int k_eff = MERGE ? min(k, Lc - n_sink) : min(k, t_hi - max(t_lo, n_sink));
+    if (slice && k_eff <= 0) {                        // nothing of the row falls into this slice
+        for (int i = threadIdx.x; i < k; i += SEL_THREADS) my_parts[i] = 0;
+        return;
+    }
     const float* __restrict__ row = P + ((int64_t)b * H + h) * ldp;
     // raw_keys: the row already holds order-preserving uint32 keys (the aggregated ranking keys of
     // the votes / max-score readings) instead of binary32 scores
     auto key_of = [raw_keys](float v) { return raw_keys ? __float_as_uint(v) : score_key(v); };
     uint32_t keys[ITEMS > 0 ? ITEMS : 1];
-    if constexpr (ITEMS > 0) {
+    int pos_of[MERGE ? ITEMS : 1];                     // MERGE: the positions that come with the keys
+    if constexpr (MERGE) {
+        const int n_cand = n_slices * k;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int t = i * SEL_THREADS + threadIdx.x;
-            const uint32_t kv_ = key_of(row[t < Lc ? t : Lc - 1]);   // clamped: loads stay unconditional
-            keys[i] = (t < Lc && t >= n_sink) ? kv_ : 0u;
+            const int sl = i * SEL_THREADS + threadIdx.x;
+            const uint64_t cv = my_parts[sl < n_cand ? sl : n_cand - 1];
+            keys[i] = sl < n_cand ? (uint32_t)(cv >> 32) : 0u;
+            pos_of[i] = (int)~(uint32_t)cv;
+        }
+    } else if constexpr (ITEMS > 0) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int t = t_lo + i * SEL_THREADS + threadIdx.x;
+            const uint32_t kv_ = key_of(row[t < t_hi ? t : t_hi - 1]);   // clamped: loads stay unconditional
+            keys[i] = (t < t_hi && t >= n_sink) ? kv_ : 0u;
         }
     }
-    // Streamed rows (ITEMS == 0) are walked in batches of SB keys per thread covering the positions
+    // Streamed rows (ITEMS <= 0) are walked in batches of SB keys per thread covering the positions
     // [t0, t0 + SB * 1024): key u of a thread is position t0 + ((u / 4) * 1024 + thread) * 4 + u % 4, so a
     // thread fetches 16 bytes at a time and a wave 1 KB per load.  Rows start 256-byte aligned and are
     // padded to a multiple of 64 entries (ldp), so a load that starts below ldp stays inside the row;
-    // the others are clamped and, like everything at or past Lc, masked (loads stay unconditional).
-    constexpr int SB = 16;
+    // the others are clamped and, like everything at or past t_hi, masked (loads stay unconditional).
+    // A slice starts at a multiple of 4096 positions, so its loads are aligned like the row's.
+    constexpr int SB = ITEMS == -1 ? 8 : 16;
     auto stream_pos = [&](int t0, int u) { return t0 + ((u >> 2) * SEL_THREADS + (int)threadIdx.x) * 4 + (u & 3); };
     // The loads of the next batch are issued before the current one is worked on.
     auto stream_issue = [&](f32x4 (&x)[SB / 4], int t0) {
@@ -471,14 +503,14 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         for (int u = 0; u < SB; ++u) {
             const int t = stream_pos(t0, u);
             const uint32_t kv_ = key_of(x[u >> 2][u & 3]);
-            kk[u] = (t < Lc && t >= n_sink) ? kv_ : 0u;
+            kk[u] = (t < t_hi && t >= n_sink) ? kv_ : 0u;
         }
     };
     // f(keys of the batch, first position of the batch) for every batch of a streamed row
     auto stream_batches = [&](auto f) {
         f32x4 x[SB / 4];
-        stream_issue(x, 0);
-        for (int t0 = 0; t0 < Lc; t0 += SB * SEL_THREADS) {
+        stream_issue(x, t_lo);
+        for (int t0 = t_lo; t0 < t_hi; t0 += SB * SEL_THREADS) {
             uint32_t kk[SB];
             stream_take(x, kk, t0);
             stream_issue(x, t0 + SB * SEL_THREADS);    // past the row's end: clamped loads, never used
@@ -490,7 +522,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         if constexpr (ITEMS > 0) {
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i) {
-                f(keys[i], i * SEL_THREADS + (int)threadIdx.x);
+                f(keys[i], MERGE ? pos_of[i] : t_lo + i * SEL_THREADS + (int)threadIdx.x);
             }
         } else {
             stream_batches([&](const uint32_t (&kk)[SB], int t0) {
@@ -508,7 +540,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     //    A streamed row keeps the maxima of 8 disjoint groups of the thread's candidates instead
     //    (one instruction per key): distinct candidates again, so the same argument holds, and
     //    with 8192 group maxima the bound is about as tight.
-    constexpr int MG = ITEMS > 0 ? MTOP : 8;
+    constexpr int MG = ITEMS > 0 ? MTOP : ITEMS == -1 ? 4 : 8;
     uint32_t top[MG];
 #pragma unroll
     for (int j = 0; j < MG; ++j) top[j] = 0u;
@@ -589,7 +621,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
     __syncthreads();
     int listable = 0;
     bool listed = false;
-    if constexpr (ITEMS == 0) {
+    if constexpr (ITEMS <= 0) {
         // one walk does both: each batch is counted into the histogram, the wave reserves list
         // slots for the batch's candidates and writes them (in arbitrary order; what is selected
         // from the list does not depend on it)
@@ -647,6 +679,10 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(const float* __restri
         });
     } else {
         finish(scan);
+    }
+    if (slice) {                                      // the slice's k best, in any order; the merge ranks
+        for (int i = threadIdx.x; i < k; i += SEL_THREADS) my_parts[i] = i < k_eff ? sort_buf[i] : 0;
+        return;
     }
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();

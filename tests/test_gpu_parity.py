@@ -507,6 +507,27 @@ def test_planted_heavy_keys_are_selected_on_gpu():
         assert set(planted[b]) <= set(idx[b])
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_few_long_ragged_rows_are_ranked_in_slices(mode):
+    """Few rows longer than 32768 candidates: the per-head top-k cuts a row into slices and merges their picks.
+    One sequence is so much shorter that its last slice is empty; equal scores sit on both sides of a slice
+    boundary; the votes / max-score rankings rank their one key row per sequence the same way."""
+    w = small(f"slices{mode}", n_q_heads=8, n_kv_heads=8, batch=2, seq_len=90000, lengths=(90000, 41000),
+              budget=512, window=128)
+
+    def dup(k):
+        k[:, :, 30000:36000] = k[:, :, 0:6000]           # 6000 scores again, across the first slice boundary
+    _with_keys(w, dup, rank_mode=mode)
+
+
+def test_many_rows_take_the_lean_streamed_topk():
+    """512 rows of more than 8192 candidates: the per-head top-k runs its register-lean streamed form, two rows
+    at a time per CU (ragged lengths, so that rows end inside a batch of keys)."""
+    w = small("manyrows", batch=16, seq_len=9700, min_seq_len=8400, budget=512, window=128, n_planted=7)
+    inp, r, sched = run_and_check(w)
+    check_attention(inp, r, 1, LAYER_SPARSE, seqs=[0, 9])
+
+
 def test_decode_step_with_different_length_bounds_per_layer():
     """Layers of one step may carry different host-side bounds max_seq_len (here 4096 / 4097 / 4096 around a
     place where the attention kernels' tiling changes); the workspace is sized once, for the largest."""
