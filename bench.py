@@ -26,8 +26,10 @@ workload with
     one selection, one sparse layer; whole step when that is short), split by stage, with the
     core count; c1 also single-threaded.
 
-`stream_read_probe` is the read rate of a plain streaming kernel measured in the same run: the
-practical ceiling to set beside the nominal peak.
+`traffic_probes` are the read rates of kernels that only move data, measured in the same run: a plain
+streaming read, gathered 256-byte rows, and a streaming read with a few per cent of writes (scattered,
+and in workgroup bursts) -- the practical ceilings to set beside the nominal peak for full attention,
+sparse attention and the selection layer's pass.
 """
 import argparse
 import ctypes
@@ -72,7 +74,7 @@ def parse():
                     help="skip the head-to-head comparison (every head attends its own top-k instead of the unified set)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the HIP-event pass (use under rocprofv3 to keep the trace to the timed steps)")
-    ap.add_argument("--no-probe", action="store_true", help="skip the streaming-read probe")
+    ap.add_argument("--no-probe", action="store_true", help="skip the traffic probes")
     return ap.parse_args()
 
 
@@ -278,30 +280,42 @@ def cpu_baseline(inp, w, sched, single_thread_too=False):
     return base
 
 
-def stream_read_probe(torch, cb):
-    """Read rate of a plain streaming kernel over 4 GiB (far beyond the 256 MB last-level cache)."""
+def traffic_probes(torch, cb):
+    """What the memory system gives the access patterns of the attention kernels without their arithmetic
+    (4 GiB each, far beyond the 256 MB last-level cache): a plain streaming read; 256-byte rows gathered with
+    irregular gaps (sparse attention); a streaming read with 1/32 of its volume written back as scattered
+    256-byte runs, and with the same volume written in workgroup bursts (the selection layer's pass, which
+    stores the scores)."""
     n = 1 << 32
     src = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     src.fill_(1)
+    dst = torch.zeros((n >> 5) + (1 << 20), dtype=torch.uint8, device="cuda:0")
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-    for _ in range(2):
-        cb.probe_stream_read(src, sink)
-    torch.cuda.synchronize()
-    cb.profile_reset()
-    cb.profile_enable(True)
+    runs = {"stream_read": (lambda: cb.probe_stream_read(src, sink), "probe_stream_read_kernel", n),
+            "gathered_rows_read": (lambda: cb.probe_traffic(1, src, dst), "probe_traffic_kernel<gather>", n >> 2),
+            "stream_read_with_scattered_writes": (lambda: cb.probe_traffic(2, src, dst), "probe_traffic_kernel<scattered writes>", n),
+            "stream_read_with_burst_writes": (lambda: cb.probe_traffic(3, src, dst), "probe_traffic_kernel<burst writes>", n)}
+    out = {}
     reps = 10
-    for _ in range(reps):
-        cb.probe_stream_read(src, sink)
-    torch.cuda.synchronize()
-    p = cb.profile_read()["probe_stream_read_kernel"]
-    cb.profile_enable(False)
-    cb.profile_reset()
-    us = p["total_ms"] * 1e3 / p["calls"]
-    del src
+    for label, (fn, kname, nbytes) in runs.items():
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        cb.profile_reset()
+        cb.profile_enable(True)
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        p = cb.profile_read()[kname]
+        cb.profile_enable(False)
+        cb.profile_reset()
+        us = p["total_ms"] * 1e3 / p["calls"]
+        gbs = nbytes / (us * 1e-6) / 1e9
+        out[label] = {"kernel": kname, "bytes_read": nbytes, "avg_us": round(us, 2), "read_GBs": round(gbs, 1),
+                      "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "launches": reps}
+    del src, dst
     torch.cuda.empty_cache()
-    gbs = n / (us * 1e-6) / 1e9
-    return {"kernel": "probe_stream_read_kernel", "bytes": n, "avg_us": round(us, 2), "GBs": round(gbs, 1),
-            "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "launches": reps}
+    return out
 
 
 def measure(name, args, torch, acc, cb, wl, StepRunner):
@@ -438,7 +452,7 @@ def main():
         if n not in wl.WORKLOADS:
             raise SystemExit(f"unknown workload {n}: choose from {sorted(wl.WORKLOADS)}")
     t_start = time.perf_counter()
-    probe = None if args.no_probe else stream_read_probe(torch, cb)
+    probe = None if args.no_probe else traffic_probes(torch, cb)
     configs = {}
     for n in names:
         t0 = time.perf_counter()
@@ -459,7 +473,7 @@ def main():
         "step_achieved_GBs": head["step_achieved_GBs"],
         "roofline": roofline,
         "cpu_baseline": head.get("cpu_baseline"),
-        "stream_read_probe": probe,
+        "traffic_probes": probe,
         "configs": configs,
         "bench_seconds": round(time.perf_counter() - t_start, 1),
     }

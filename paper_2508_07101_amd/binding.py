@@ -25,7 +25,7 @@ EXPORTS = [
     "cusa_select_per_head", "cusa_sparse_attn_per_head", "cusa_attention_recall", "cusa_select_layer",
     "cusa_full_attn", "cusa_decode_step", "cusa_strerror", "cusa_profile_num_kernels",
     "cusa_profile_kernel_name", "cusa_profile_enable", "cusa_profile_reset", "cusa_profile_read",
-    "cusa_build_id", "cusa_probe_stream_read", "cusa_sparse_attn_noalloc", "cusa_noalloc_max_scratch_bytes",
+    "cusa_build_id", "cusa_probe_stream_read", "cusa_probe_traffic", "cusa_sparse_attn_noalloc", "cusa_noalloc_max_scratch_bytes",
 ]
 
 
@@ -121,6 +121,8 @@ def load():
     lib.cusa_noalloc_max_scratch_bytes.restype = sz
     lib.cusa_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.cusa_probe_stream_read.restype = ctypes.c_int
+    lib.cusa_probe_traffic.argtypes = [i32, vp, sz, vp, sz, vp]
+    lib.cusa_probe_traffic.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -275,6 +277,12 @@ def probe_stream_read(src: torch.Tensor, sink: torch.Tensor):
     """Enqueue the streaming-read probe over the bytes of src (benchmark support)."""
     _check(load().cusa_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()),
            "cusa_probe_stream_read")
+
+
+def probe_traffic(pattern: int, src: torch.Tensor, dst: torch.Tensor):
+    """Enqueue a traffic probe (1 gathered rows, 2 stream + scattered writes, 3 stream + burst writes)."""
+    _check(load().cusa_probe_traffic(pattern, _ptr(src), src.numel() * src.element_size(), _ptr(dst),
+                                     dst.numel() * dst.element_size(), _stream()), "cusa_probe_traffic")
 
 
 # ---- per-kernel timing ---------------------------------------------------------

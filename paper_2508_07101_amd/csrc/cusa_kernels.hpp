@@ -443,7 +443,20 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
     __shared__ int n_out, n_list;
     int* hist = reinterpret_cast<int*>(sort_buf);     // 2048 ints = 8 KB <= NSORT * 8
 
-    const int h = blockIdx.x, b = blockIdx.y;
+    // Workgroups go to the 8 XCDs round-robin in launch order.  The heads of a sequence write the same
+    // lines of the rank-major output (entry (j, h) next to (j, h+1)); with eight sequences or more, all
+    // heads of a sequence are put on one XCD, whose L2 then merges their 4-byte stores into whole
+    // lines instead of each XCD writing its own fragments of every line (c5: 104 MB written for a 13 MB
+    // output before).
+    int h = blockIdx.x, b = blockIdx.y;
+    {
+        const int B = gridDim.y, lin = blockIdx.x + H * blockIdx.y;
+        if (lin < (B / 8) * 8 * H) {
+            const int within = lin % (8 * H);
+            b = (lin / (8 * H)) * 8 + (within & 7);
+            h = within >> 3;
+        }
+    }
     const int L = seq_lens[b];
     if (L <= budget) return;
     const int Lc = L - window;
@@ -1175,7 +1188,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int WAVE_LDS = TILE * KSLOTS * 16;      // bytes of a wave's tile buffer
     static_assert(WAVE_LDS >= GQ * D * 4, "the K tile buffer must hold a wave's partial accumulators");
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[ATTN_WAVES * WAVE_LDS];
-    // this wave's K rows: chunk c of row r at slot c ^ (r & 7); scoring variant: chunk c (of the half) at slot c ^ ((r >> 1) & 7)
+    // this wave's K rows: chunk c of row r at slot c ^ (r & 7) (a swizzle over all sixteen slots, c ^ (r & 15),
+    // removes the remaining two-way bank conflicts and was measured: no faster); scoring variant: chunk c
+    // (of the half) at slot c ^ ((r >> 1) & 7)
     u32x4* const ktile = reinterpret_cast<u32x4*>(smem_raw) + wave_base_of(threadIdx.x) * (TILE * KSLOTS);
     __shared__ float sm_m[ATTN_WAVES][GQ];
     __shared__ float sm_l[ATTN_WAVES][GQ];
@@ -1718,6 +1733,65 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_stream_read_kernel(const 
     for (; i < n_vec; i += stride) fold ^= __builtin_nontemporal_load(&src[i]);
     const uint32_t f = fold.x ^ fold.y ^ fold.z ^ fold.w;
     if (f == 0x9e3779b9u) *sink = f;                 // keeps the loads alive; practically never taken
+}
+
+// Traffic probes (benchmark support): the memory system's rate for the access patterns of the attention
+// kernels, without their arithmetic.  A workgroup of four waves walks chunks of 32 tiles; a wave reads a
+// tile of 32 KB with 32 loads of 16 bytes per lane in flight (what K and V of 64 tokens are), then
+//   PATTERN 1: nothing else -- but the tile is 128 rows of 256 bytes gathered from a region four times as
+//              large: row 4 j + (hash(j) mod 4), ascending with irregular gaps like a sorted token list;
+//   PATTERN 2: streams its tile and writes 1 KB of results as four runs of 256 bytes in rows far apart,
+//              right away (what a scoring pass does that stores every tile's scores);
+//   PATTERN 3: streams its tile and keeps the 1 KB in LDS; the workgroup writes the chunk's 32 KB in one
+//              burst (four runs of 8 KB) when the chunk is done.
+// dst takes the results of patterns 2 and 3: one float per 128 bytes read.
+constexpr int PROBE_CHUNK_TILES = 32;
+
+template <int PATTERN>
+__global__ __launch_bounds__(256) void probe_traffic_kernel(const u32x4* __restrict__ src, float* __restrict__ dst,
+                                                             int64_t n_chunks) {
+    __shared__ f32x4 stage[PATTERN == 3 ? PROBE_CHUNK_TILES * 64 : 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+        for (int j = 0; j < PROBE_CHUNK_TILES / 4; ++j) {
+            const int64_t t = ch * PROBE_CHUNK_TILES + j * 4 + wave;   // tile
+            u32x4 v[32];
+            if (PATTERN == 1) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    const int64_t jrow = t * 128 + i * 4 + (lane >> 4);
+                    const uint32_t hsh = (uint32_t)jrow * 2654435761u;
+                    v[i] = src[(jrow * 4 + (hsh >> 30)) * 16 + (lane & 15)];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) v[i] = src[t * 2048 + i * 64 + lane];
+            }
+            u32x4 f = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 32; ++i) f ^= v[i];
+            const f32x4 o = {(float)f.x, (float)f.y, (float)f.z, (float)f.w};
+            if (PATTERN == 2) {
+                const int64_t g = t >> 9, col = (t & 511) * 64 + lane;
+#pragma unroll
+                for (int h = 0; h < 4; ++h) dst[(g * 4 + h) * 32768 + col] = o[h];
+            } else if (PATTERN == 3) {
+                stage[(j * 4 + wave) * 64 + lane] = o;
+            } else if (f.x == 0x9e3779b9u) {
+                dst[0] = o[0];                           // keeps the loads alive; practically never taken
+            }
+        }
+        if (PATTERN == 3) {
+            __syncthreads();
+            constexpr int PER = PROBE_CHUNK_TILES * 64 / 4;   // 16-byte words per run: four runs of 8 KB
+            for (int i = threadIdx.x; i < PROBE_CHUNK_TILES * 64; i += 256) {
+                const int q = i / PER, w = i % PER;
+                f32x4* const p = reinterpret_cast<f32x4*>(dst) + ((ch / 16) * 4 + q) * (16 * (int64_t)PER) + (ch % 16) * PER + w;
+                __builtin_nontemporal_store(stage[i], p);
+            }
+            __syncthreads();
+        }
+    }
 }
 
 // Attention recall (Eq. 3): the share of a head's softmax mass that falls on its token set.  With

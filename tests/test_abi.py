@@ -156,3 +156,14 @@ def test_probe_rejects_bad_arguments():
     assert lib.cusa_probe_stream_read(fake, 8, fake, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_probe_stream_read(ctypes.c_void_p(0x10008), 1 << 20, fake, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_probe_stream_read(fake, 1 << 20, None, None) == cb.ERR_INVALID_ARG
+
+
+def test_traffic_probe_rejects_bad_arguments():
+    lib = cb.load()
+    fake = ctypes.c_void_p(0x10000)
+    assert lib.cusa_probe_traffic(0, fake, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG      # no such pattern
+    assert lib.cusa_probe_traffic(4, fake, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_probe_traffic(2, None, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG
+    assert lib.cusa_probe_traffic(2, fake, 1 << 19, fake, 1 << 20, None) == cb.ERR_INVALID_ARG      # under one chunk
+    assert lib.cusa_probe_traffic(1, fake, 1 << 21, fake, 1 << 20, None) == cb.ERR_INVALID_ARG      # gather needs 4 MiB
+    assert lib.cusa_probe_traffic(3, fake, 1 << 25, fake, 1 << 19, None) == cb.ERR_INVALID_ARG      # results do not fit
