@@ -246,7 +246,11 @@ def cpu_baseline(inp, w, sched, single_thread_too=False):
     base = {"unit": "us", "cores": cores, "kind": "oracle",
             "sequence0_one_layer_s": {"full_attention": round(t_full, 4), "selection": round(t_sel, 4),
                                       "sparse_attention": round(t_sparse, 5), "context": inp.seq_lens_host[0]}}
-    if single_thread_too:
+
+    def single_thread(base):
+        """Last, because changing the thread count makes the OpenMP runtime rebuild its pool."""
+        if not single_thread_too:
+            return base
         _set_omp_threads(1)
         s_full, _ = timed(lambda: oracle.attention(q, K, V))
         s_sel, _ = timed(lambda: oracle.select(q, K, w.budget, w.window, w.topk_per_head))
@@ -255,29 +259,31 @@ def cpu_baseline(inp, w, sched, single_thread_too=False):
         base["single_thread_s"] = {"full_attention": round(s_full, 4), "selection": round(s_sel, 4),
                                    "sparse_attention": round(s_sparse, 5),
                                    "step": round(n_full * s_full + s_sel + n_sparse * s_sparse, 4)}
+        return base
+
     if projected > 20.0:
         base.update(value=round(projected * 1e6, 1), stage_seconds={k: round(v, 4) for k, v in stage.items()},
                     sample=(f"sequence 0 of {w.batch}: one full-attention layer, one selection, one sparse layer; "
                             f"projected to {n_full} full + 1 select + {n_sparse} sparse layers and to all sequences by length"))
-        return base
+        return single_thread(base)
     stage = {"full_attention_s": 0.0, "selection_s": 0.0, "sparse_attention_s": 0.0}
     rho = [None] * w.batch
     for i, kind in enumerate(sched):
         for b in range(w.batch):
-            q, K, V = _host_view(inp, i, b)                          # device -> host copy, not timed
+            qi, Ki, Vi = _host_view(inp, i, b)                       # device -> host copy, not timed
             if kind == 2:
-                dt, _ = timed(lambda: oracle.attention(q, K, V, rho[b]))
+                dt, _ = timed(lambda: oracle.attention(qi, Ki, Vi, rho[b]))
                 stage["sparse_attention_s"] += dt
             else:
-                dt, _ = timed(lambda: oracle.attention(q, K, V))
+                dt, _ = timed(lambda: oracle.attention(qi, Ki, Vi))
                 stage["full_attention_s"] += dt
                 if kind == 1:
-                    d2, rho[b] = timed(lambda: oracle.select(q, K, w.budget, w.window, w.topk_per_head))
+                    d2, rho[b] = timed(lambda: oracle.select(qi, Ki, w.budget, w.window, w.topk_per_head))
                     stage["selection_s"] += d2
     base.update(value=round(sum(stage.values()) * 1e6, 1), stage_seconds={k: round(v, 4) for k, v in stage.items()},
                 sample=f"the whole step: all {len(sched)} layers of all {w.batch} sequences, oracle calls only "
                        f"(host copies of the inputs not timed)")
-    return base
+    return single_thread(base)
 
 
 def traffic_probes(torch, cb):
