@@ -107,7 +107,8 @@ typedef struct {
  *   scores    float  [batch][n_q_heads][ld_scores]   P = q.K^T over [0, L_b-W)
  *   rho_head  int32  [batch][k][n_q_heads]           ranked picks, RANK-MAJOR:
  *             entry (b, j, h) is head h's rank-j pick; valid for j < min(k, L_b-W)
- * Both are defined only for sequences with L_b > K.  (With rank_mode VOTES or
+ * Both are defined only for sequences with L_b > K; scores also depends on filtered_select below.
+ * (With rank_mode VOTES or
  * MAX_SCORE the workspace also holds one ranking key per candidate position and the
  * unified ranked list; they are internal.) */
 typedef struct {
@@ -116,6 +117,10 @@ typedef struct {
     size_t  rho_head_offset;
     int32_t k;                      /* topk_per_head after resolving 0 -> K-W */
     size_t  total_bytes;
+    int32_t filtered_select;        /* 1: a selection LAYER of this size (cusa_select_layer, a SELECT layer of
+                                       cusa_decode_step) keeps only the scores that can reach a head's top-k
+                                       and writes no score array; `scores` is then defined after cusa_select
+                                       only.  rho_head, idx and cnt are the same either way. */
 } cusa_ws_layout;
 
 /* Bytes of device workspace any of the calls below needs for `params` and

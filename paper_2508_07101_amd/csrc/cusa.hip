@@ -19,13 +19,13 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_PROBE_GATHER, KID_PROBE_RW_SCATTER, KID_PROBE_RW_BURST, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_PROBE_GATHER, KID_PROBE_RW_SCATTER, KID_PROBE_RW_BURST, KID_SAMPLE_THRESHOLD, KID_TOPK_FILTERED, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
                                              "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel", "topk_kernel<slice>",
                                              "topk_kernel<merge>", "probe_traffic_kernel<gather>", "probe_traffic_kernel<scattered writes>",
-                                             "probe_traffic_kernel<burst writes>"};
+                                             "probe_traffic_kernel<burst writes>", "sample_threshold_kernel", "topk_kernel<filtered>"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -215,8 +215,48 @@ int plan_topk_slices(int64_t rows, int lc_max, int k) {
     return s < 1 ? 1 : (int)s;
 }
 
+// Sampling plan of the filtered fast path for sequences of up to lc candidate positions: every
+// tile_step-th tile of 64 tokens, n_slots sample slots per head.
+struct SamplePlan {
+    int tile_step, n_slots;
+};
+SamplePlan plan_sample(int64_t lc) {
+    const int64_t tiles_all = (lc + SCORE_ROWS - 1) / SCORE_ROWS;
+    int64_t step = (tiles_all + SAMPLE_MAX_TILES - 1) / SAMPLE_MAX_TILES;
+    if (step < SAMPLE_STEP) step = SAMPLE_STEP;
+    return {(int)step, (int)((tiles_all + step - 1) / step) * SCORE_ROWS};
+}
+int filter_cap_for(int k) { return k <= 2048 ? 4096 : 8192; }
+size_t sample_lds_bytes(int g, int n_slots) { return (size_t)g * ((size_t)n_slots + THR_BINS) * 4; }
+
+// Whether a selection layer takes the filtered fast path (sample_threshold_kernel): it pays where the
+// scores of the layer are many (tens of MB of them) and a head keeps a small share of its candidates;
+// it needs the default ranking (the max-score reading looks picks' scores up in P, which the fast path
+// does not write), a k the merge form of the top-k holds in registers, query groups of at most 4 heads
+// (the filtered pass of a group of 8 does not fit the register file), and a sample dense enough that
+// what a head of the longest sequence is expected to keep fits its buffer with room to spare.
+constexpr int64_t FILTER_MIN_SCORES = (int64_t)8 << 20;
+// Everything but the sample's density: once true it stays true for longer bounds, so the workspace laid
+// out for a capacity serves every shorter bound.
+bool filter_buffers_needed(const cusa_params* p, int max_seq_len) {
+    const int64_t lc = (int64_t)max_seq_len - p->window;
+    const int k = resolved_k(p);
+    return p->rank_mode == CUSA_RANK_FIRST_OCCURRENCE && p->n_q_heads / p->n_kv_heads <= 4 && k >= 1 && k <= 4096 &&
+           lc >= 4 * (int64_t)k && (int64_t)p->batch * p->n_q_heads * lc >= FILTER_MIN_SCORES;
+}
+bool filtered_select(const cusa_params* p, int max_seq_len) {
+    if (!filter_buffers_needed(p, max_seq_len)) return false;
+    const int64_t lc = (int64_t)max_seq_len - p->window;
+    const int k = resolved_k(p);
+    const float n = (float)(lc - p->n_sink), n_s = n / (float)plan_sample(lc).tile_step;
+    const int j = filter_sample_rank((float)k, n, n_s);
+    return filter_kept_bound(n, n_s, (float)j + 2.0f) <= 0.9f * (float)filter_cap_for(k);
+}
+
 struct WsLayout {
     size_t scores, rho_head, part_acc, part_ml, agg, rho_rank, lse, out_tmp, topk_parts, total;
+    size_t f_thr, f_cnt, f_fail, f_nfailed, f_cand;           // the selection's filtered fast path
+    int filter_cap;                                           // 0: not laid out
     int64_t ldp;
     int k;
     int max_splits;
@@ -254,6 +294,16 @@ WsLayout make_layout(const cusa_params* p, int max_seq_len) {
         w.topk_parts = off;
         off += align256(n * 8);
     }
+    w.filter_cap = 0;
+    w.f_thr = w.f_cnt = w.f_fail = w.f_nfailed = w.f_cand = off;
+    if (filter_buffers_needed(p, max_seq_len)) {
+        w.filter_cap = filter_cap_for(w.k);
+        w.f_thr = off;      off += align256((size_t)(B * H) * 4);
+        w.f_cnt = off;      off += align256((size_t)(B * H) * 4);
+        w.f_fail = off;     off += align256((size_t)(B * H) * 4);
+        w.f_nfailed = off;  off += 256;
+        w.f_cand = off;     off += align256((size_t)(B * H) * w.filter_cap * 8);
+    }
     w.lse = off;      off += align256((size_t)(B * H * 2) * 4);        // recall: denominators over the set and over all tokens
     w.out_tmp = off;  off += align256((size_t)(B * H * D) * 2);        // recall: the attention outputs nobody reads
     w.total = off;
@@ -287,6 +337,7 @@ struct ScoreOut {
     float* P = nullptr;     // nullptr: plain attention
     int64_t ldp = 0;
     int window = 0;
+    FilterState filter = {};   // thr set: the pass keeps the candidates at or above the heads' thresholds instead of writing P
 };
 
 struct AttnArgs {
@@ -307,15 +358,15 @@ struct AttnArgs {
     ScoreOut score;
 };
 
-template <int GQ, int TI, bool SPARSE, bool SCORE>
+template <int GQ, int TI, bool SPARSE, bool SCORE, bool FILTER = false>
 void launch_attn_partial(const AttnArgs& a) {
     const int kid = SPARSE ? KID_ATTN_SPARSE : SCORE ? KID_ATTN_SELECT : KID_ATTN_FULL;
     if (a.paged)
-        launch(kid, attn_kernel<GQ, TI, SPARSE, true, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.view);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, true, SCORE, false, FILTER>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.score.filter, a.view);
     else
-        launch(kid, attn_kernel<GQ, TI, SPARSE, false, SCORE>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
-               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.view);
+        launch(kid, attn_kernel<GQ, TI, SPARSE, false, SCORE, false, FILTER>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens, a.q,
+               a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0, a.score.filter, a.view);
 }
 
 // Sparse attention with one token list per query head: grid.y counts query heads.
@@ -323,18 +374,25 @@ template <int TI>
 void launch_attn_per_head(const AttnArgs& a, int H, int hshift) {
     if (a.paged)
         launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, true, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
-               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, a.view);
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, FilterState{}, a.view);
     else
         launch(KID_ATTN_PER_HEAD, attn_kernel<1, TI, true, false, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt,
-               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, a.view);
+               a.view.seq_lens, a.q, a.budget, a.n_splits, a.chunk, H, a.scale, a.pa, a.pm, a.out, a.lse, nullptr, 0, 0, hshift, FilterState{}, a.view);
 }
 
 template <int GQ, bool SPARSE>
 void launch_attn_ti(int ti, const AttnArgs& a) {
     if constexpr (!SPARSE) {
         if (a.score.P) {                              // the scoring chain repeats work for tiles under 64 tokens: always the wider tile
-            if (ti == 16) launch_attn_partial<GQ, 16, false, true>(a);
-            else launch_attn_partial<GQ, 8, false, true>(a);
+            if (a.score.filter.thr) {                 // groups of up to 4 only (filtered_select)
+                if constexpr (GQ <= 4) {
+                    if (ti == 16) launch_attn_partial<GQ, 16, false, true, true>(a);
+                    else launch_attn_partial<GQ, 8, false, true, true>(a);
+                }
+            } else {
+                if (ti == 16) launch_attn_partial<GQ, 16, false, true>(a);
+                else launch_attn_partial<GQ, 8, false, true>(a);
+            }
             return;
         }
     }
@@ -457,6 +515,13 @@ void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
 
 // True once the current device's kernels hold their LDS grants.  Without a device (a host that
 // only sizes workspaces) nothing is done and false is returned.
+template <int GQ>
+bool grant_sample() {
+    const size_t bytes = sample_lds_bytes(GQ, SAMPLE_MAX_TILES * SCORE_ROWS);
+    return grant_lds(reinterpret_cast<const void*>(sample_threshold_kernel<GQ, false>), bytes) &&
+           grant_lds(reinterpret_cast<const void*>(sample_threshold_kernel<GQ, true>), bytes);
+}
+
 bool device_ready() {
     static std::mutex mu;
     static bool ready[MAX_DEVICES] = {false};
@@ -470,7 +535,8 @@ bool device_ready() {
     const bool ok = grant_topk_items<4>() && grant_topk_items<8>() && grant_topk_items<16>() && grant_topk_items<32>() &&
                     grant_topk_items<0>() && grant_topk_items<-1>() && grant_topk_items<4, true>() &&
                     grant_topk_items<8, true>() && grant_topk_items<16, true>() && grant_lds(reinterpret_cast<const void*>(union_kernel), SEL_LDS_MAX) &&
-                    grant_lds(reinterpret_cast<const void*>(per_head_rho_kernel), SEL_LDS_MAX);
+                    grant_lds(reinterpret_cast<const void*>(per_head_rho_kernel), SEL_LDS_MAX) && grant_sample<1>() &&
+                    grant_sample<2>() && grant_sample<4>();
     void* ptr = nullptr;
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
         (void)hipGetLastError();
@@ -494,13 +560,15 @@ struct TopkArgs {
     int H, k, budget, window, raw, n_sink;
     uint64_t* parts;
     int slice_len, n_slices;
+    const int32_t* only_rows = nullptr;   // rank only the rows whose flag is set
+    FilterState filter = {};              // merge form: rank the candidates the filtered pass kept
 };
 
 template <int ITEMS, int MTOP, bool MERGE>
 cusa_status launch_topk_m(const TopkArgs& a) {
     const size_t shmem = topk_lds_bytes<ITEMS, MTOP>();
-    launch(MERGE ? KID_TOPK_MERGE : a.parts ? KID_TOPK_SLICE : KID_TOPK, topk_kernel<ITEMS, MTOP, MERGE>, a.grid, SEL_THREADS, shmem, a.s, a.P, a.ldp, a.seq_lens, a.rho_head, a.H, a.k,
-           a.budget, a.window, a.raw, a.n_sink, a.parts, a.slice_len, a.n_slices);
+    launch(MERGE ? (a.filter.thr ? KID_TOPK_FILTERED : KID_TOPK_MERGE) : a.parts ? KID_TOPK_SLICE : KID_TOPK, topk_kernel<ITEMS, MTOP, MERGE>, a.grid, SEL_THREADS, shmem, a.s, a.P, a.ldp, a.seq_lens, a.rho_head, a.H, a.k,
+           a.budget, a.window, a.raw, a.n_sink, a.parts, a.slice_len, a.n_slices, a.only_rows, a.filter);
     return launch_status();
 }
 
@@ -517,8 +585,10 @@ cusa_status launch_topk(const TopkArgs& a) {
 // Ranked top-k of every row of P: rows (b, h) of length L_b - W, output rank-major out[b][j][h].
 // raw: the rows hold uint32 keys instead of scores.  parts: room for rows * slices * k composites.
 cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, int64_t ldp, const int32_t* seq_lens,
-                     int32_t* out, int k, int budget, int window, int raw, int n_sink, uint64_t* parts) {
+                     int32_t* out, int k, int budget, int window, int raw, int n_sink, uint64_t* parts,
+                     const int32_t* only_rows = nullptr) {
     TopkArgs a = {dim3(H, B), s, P, ldp, seq_lens, out, H, k, budget, window, raw, n_sink, nullptr, 0, 1};
+    a.only_rows = only_rows;
     const int n_slices = plan_topk_slices((int64_t)B * H, lc_max, k);
     int n_cand = lc_max;                                  // candidates a workgroup walks
     if (n_slices > 1) {
@@ -547,45 +617,59 @@ cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, in
 
 template <int GQ>
 void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
-                  int H, int budget, int window, int tiles_per_seq, int n_tiles) {
+                  int H, int budget, int window, int tiles_per_seq, int n_tiles, const int32_t* only_failed,
+                  const int32_t* n_failed) {
     if (paged)
-        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles, view);
+        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles,
+               only_failed, n_failed, view);
     else
-        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles, view);
+        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles,
+               only_failed, n_failed, view);
+}
+
+// P = q.K^T over the candidate range.
+cusa_status run_score(const cusa_params* p, const void* q, const cusa_kv* kv, float* P, int64_t ldp, hipStream_t s,
+                      const int32_t* only_failed, const int32_t* n_failed) {
+    const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
+    const KvView view = make_view(p, kv);
+    const bool paged = kv->layout == CUSA_KV_PAGED;
+    const uint16_t* qf = static_cast<const uint16_t*>(q);
+    const int lc_max = kv->max_seq_len - p->window;
+    const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
+    const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
+    if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
+    const int n_tiles = (int)n_tiles64;
+    const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
+    const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
+    switch (g) {
+        case 1: launch_score<1>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
+        case 2: launch_score<2>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
+        case 4: launch_score<4>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
+        default: launch_score<8>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
+    }
+    return launch_status();
 }
 
 // scores_ready: P was already written by the layer's attention pass (cusa_decode_step).
 // per_head: idx is [B][H][budget], every head keeps its own first K-W picks (head-to-head selection).
 cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, int32_t* idx, int32_t* cnt, void* ws,
-                       const WsLayout& w, hipStream_t s, bool scores_ready = false, bool per_head = false) {
-    const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
-    const KvView view = make_view(p, kv);
-    const bool paged = kv->layout == CUSA_KV_PAGED;
-    const uint16_t* qf = static_cast<const uint16_t*>(q);
+                       const WsLayout& w, hipStream_t s, bool scores_ready = false, bool per_head = false,
+                       const FilterState* redo = nullptr) {
+    const int H = p->n_q_heads, B = p->batch;
+    // redo: the filtered fast path has ranked most heads already; only the flagged ones are scored and ranked here
+    const int32_t* only_failed = redo ? redo->fail : nullptr;
+    const int32_t* n_failed = redo ? redo->n_failed : nullptr;
     float* P = ws_ptr<float>(ws, w.scores);
     int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
 
     if (kv->max_seq_len > p->budget) {            // otherwise no sequence can need scoring
         const int lc_max = kv->max_seq_len - p->window;
         if (!scores_ready) {
-            const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
-            const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
-            if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
-            const int n_tiles = (int)n_tiles64;
-            const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
-            const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
-            {
-                switch (g) {
-                    case 1: launch_score<1>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                    case 2: launch_score<2>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                    case 4: launch_score<4>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                    default: launch_score<8>(paged, grid, s, view, qf, P, w.ldp, H, p->budget, p->window, tiles_per_seq, n_tiles); break;
-                }
-            }
-            if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+            const cusa_status st = run_score(p, q, kv, P, w.ldp, s, only_failed, n_failed);
+            if (st != CUSA_OK) return st;
         }
         cusa_status st = run_topk(lc_max, B, H, s, P, w.ldp, kv->seq_lens, rho_head, w.k, p->budget, p->window, 0, p->n_sink,
-                                  ws_ptr<uint64_t>(ws, w.topk_parts));
+                                  ws_ptr<uint64_t>(ws, w.topk_parts), only_failed);
         if (st != CUSA_OK) return st;
     }
     {
@@ -621,6 +705,29 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
     return launch_status();
 }
 
+template <int GQ>
+void launch_sample_threshold_g(const cusa_params* p, const void* q, const cusa_kv* kv, const SamplePlan& sp,
+                               const FilterState& f, int k, hipStream_t s) {
+    const KvView view = make_view(p, kv);
+    const dim3 grid(p->n_kv_heads, p->batch);
+    const size_t shmem = sample_lds_bytes(GQ, sp.n_slots);
+    const uint16_t* qf = static_cast<const uint16_t*>(q);
+    if (kv->layout == CUSA_KV_PAGED)
+        launch(KID_SAMPLE_THRESHOLD, sample_threshold_kernel<GQ, true>, grid, SEL_THREADS, shmem, s, qf, p->n_q_heads, k, p->budget,
+               p->window, sp.tile_step, sp.n_slots, f, view);
+    else
+        launch(KID_SAMPLE_THRESHOLD, sample_threshold_kernel<GQ, false>, grid, SEL_THREADS, shmem, s, qf, p->n_q_heads, k, p->budget,
+               p->window, sp.tile_step, sp.n_slots, f, view);
+}
+void launch_sample_threshold(const cusa_params* p, const void* q, const cusa_kv* kv, const SamplePlan& sp,
+                             const FilterState& f, int k, hipStream_t s) {
+    switch (p->n_q_heads / p->n_kv_heads) {           // groups of up to 4 only (filtered_select)
+        case 1: launch_sample_threshold_g<1>(p, q, kv, sp, f, k, s); break;
+        case 2: launch_sample_threshold_g<2>(p, q, kv, sp, f, k, s); break;
+        default: launch_sample_threshold_g<4>(p, q, kv, sp, f, k, s); break;
+    }
+}
+
 // A selection layer (Alg. 1): full attention for the layer's output and rho from the same q and K.
 // The pass over all tokens also writes the scores, so K is read once.
 cusa_status run_select_layer(const cusa_params* p, const void* q, const cusa_kv* kv, void* out, int32_t* idx,
@@ -630,6 +737,32 @@ cusa_status run_select_layer(const cusa_params* p, const void* q, const cusa_kv*
         score.P = ws_ptr<float>(ws, w.scores);
         score.ldp = w.ldp;
         score.window = p->window;
+    }
+    if (score.P && w.filter_cap > 0 && filtered_select(p, kv->max_seq_len)) {
+        // The filtered fast path: thresholds from a sample, the pass keeps the candidates above them, the
+        // top-k ranks among those, and whatever the guess failed for is scored and ranked the ordinary way.
+        const int H = p->n_q_heads, B = p->batch;
+        FilterState f;
+        f.thr = ws_ptr<uint32_t>(ws, w.f_thr);
+        f.cand_cnt = ws_ptr<int32_t>(ws, w.f_cnt);
+        f.fail = ws_ptr<int32_t>(ws, w.f_fail);
+        f.n_failed = ws_ptr<int32_t>(ws, w.f_nfailed);
+        f.cand = ws_ptr<uint64_t>(ws, w.f_cand);
+        f.cap = w.filter_cap;
+        f.n_sink = p->n_sink;
+        const SamplePlan sp = plan_sample((int64_t)kv->max_seq_len - p->window);
+        launch_sample_threshold(p, q, kv, sp, f, w.k, s);
+        if (launch_status() != CUSA_OK) return CUSA_ERR_LAUNCH;
+        score.filter = f;
+        cusa_status st = run_attention<false>(p, q, kv, nullptr, nullptr, kv->max_seq_len, out, ws, w, s, score);
+        if (st != CUSA_OK) return st;
+        TopkArgs a = {dim3(H, B), s, nullptr, 0, kv->seq_lens, ws_ptr<int32_t>(ws, w.rho_head), H, w.k, p->budget, p->window, 0,
+                      p->n_sink, nullptr, 0, 1};
+        a.filter = f;
+        const int items = (f.cap + SEL_THREADS - 1) / SEL_THREADS;
+        st = items <= 4 ? launch_topk<4, true>(a) : items <= 8 ? launch_topk<8, true>(a) : launch_topk<16, true>(a);
+        if (st != CUSA_OK) return st;
+        return run_select(p, q, kv, idx, cnt, ws, w, s, false, false, &f);
     }
     cusa_status st = run_attention<false>(p, q, kv, nullptr, nullptr, kv->max_seq_len, out, ws, w, s, score);
     if (st != CUSA_OK) return st;
@@ -662,6 +795,7 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
     layout->rho_head_offset = w.rho_head;
     layout->k = w.k;
     layout->total_bytes = w.total;
+    layout->filtered_select = filtered_select(params, max_seq_len) ? 1 : 0;
     return CUSA_OK;
 }
 

@@ -42,6 +42,7 @@ __device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int kvh, 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -92,11 +93,18 @@ constexpr int SCORE_WAVES = 4;
 // Forward declaration: wave-local LDS ordering (defined with the attention kernel).
 __device__ __forceinline__ void wave_lds_sync();
 
+//
+// only_failed (with its counter n_failed): only the groups that have a head whose flag is set are
+// scored, and nothing at all when the counter is zero -- the second chance of the selection's
+// filtered fast path.
 template <int GQ, bool PAGED>
 __global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t* __restrict__ q,
                                                                   float* __restrict__ P, int64_t ldp, int H,
                                                                   int budget, int window, int tiles_per_seq,
-                                                                  int n_tiles, KvView kv) {
+                                                                  int n_tiles,
+                                                                  const int32_t* __restrict__ only_failed,
+                                                                  const int32_t* __restrict__ n_failed, KvView kv) {
+    if (n_failed && *n_failed == 0) return;
     constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
     constexpr int QL = (GQ * D * 2 + 1023) / 1024;    // 16-byte q loads per lane
     __shared__ u32x4 tile_all[SCORE_WAVES][SCORE_ROWS * 16];
@@ -121,7 +129,12 @@ __global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t*
             t0 = (id - seq_head * tiles_per_seq) * SCORE_ROWS;
             const int L = kv.seq_lens[b];
             Lc = L - window;
-            if (L > budget && t0 < Lc) return id;     // L <= budget: rho = everything, nothing to score
+            if (L > budget && t0 < Lc) {              // L <= budget: rho = everything, nothing to score
+                if (!only_failed) return id;
+                int any = 0;
+                for (int hh = 0; hh < GQ; ++hh) any |= only_failed[b * H + kvh * GQ + hh];
+                if (any) return id;
+            }
         }
         return n_tiles;
     };
@@ -263,6 +276,26 @@ __device__ __forceinline__ uint32_t score_key(float s) {
     uint32_t u = __float_as_uint(s);
     if (u == 0x80000000u) u = 0;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// State of the selection's filtered fast path (sample_threshold_kernel has the account).
+struct FilterState {              // device memory of the fast path, all per (sequence, head) = row
+    uint32_t* thr;                // threshold key; 0xffffffff: keep nothing (flagged, or nothing to select)
+    int32_t* cand_cnt;            // candidates kept so far
+    int32_t* fail;                // 1: this head takes the second chance
+    int32_t* n_failed;            // number of flagged heads
+    uint64_t* cand;               // [row][cap] composites (score key << 32 | ~position), in any order
+    int32_t cap;
+    int32_t n_sink;
+};
+
+// Flags are set wherever a head's guess turns out bad; the heads are counted in one place, the top-k over
+// the kept candidates, which looks at every head once.
+__device__ __forceinline__ void flag_failed(const FilterState& f, int64_t row) { f.fail[row] = 1; }
+
+// Inverse of score_key.
+__device__ __forceinline__ float key_score(uint32_t key) {
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
 // ---------------------------------------------------------------- per-head top-k
@@ -428,11 +461,12 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
 // with zeros, in parts[row][slice][k]; the k best of a row are among the k best of its slices, so a
 // second launch (MERGE) selects and ranks among those n_slices * k composites instead of the row.
 template <int ITEMS, int MTOP, bool MERGE = false>
-__global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
+__global__ __launch_bounds__(SEL_THREADS, (ITEMS == -1 || (MERGE && ITEMS <= 4)) ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
                                                             int budget, int window, int raw_keys, int n_sink,
-                                                            uint64_t* __restrict__ parts, int slice_len, int n_slices) {
+                                                            uint64_t* __restrict__ parts, int slice_len, int n_slices,
+                                                            const int32_t* __restrict__ only_rows, FilterState flt) {
     static_assert(!MERGE || ITEMS > 0, "the composites of a merge are held in registers");
     constexpr int NSORT = MTOP * SEL_THREADS;         // k <= NSORT
     constexpr int CAP = topk_list_cap(ITEMS, MTOP);
@@ -457,11 +491,13 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
             h = within >> 3;
         }
     }
+    // only_rows: the second chance of the filtered fast path ranks the flagged heads only
+    if (only_rows && only_rows[(int64_t)b * H + h] == 0) return;
     const int L = seq_lens[b];
     if (L <= budget) return;
     const int Lc = L - window;
     // this workgroup's candidates: the positions [t_lo, t_hi) of the row (a slice of it), or -- MERGE --
-    // the composites the slices left
+    // the composites the slices left, or (flt.thr set) those the filtered pass kept for this head
     const bool slice = !MERGE && parts != nullptr;
     const int t_lo = slice ? (int)blockIdx.z * slice_len : 0;
     const int t_hi = slice ? min(Lc, t_lo + slice_len) : Lc;
@@ -479,11 +515,26 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
     uint32_t keys[ITEMS > 0 ? ITEMS : 1];
     int pos_of[MERGE ? ITEMS : 1];                     // MERGE: the positions that come with the keys
     if constexpr (MERGE) {
-        const int n_cand = n_slices * k;
+        int n_cand = n_slices * k;
+        const uint64_t* __restrict__ src = my_parts;
+        if (flt.thr) {
+            const int64_t row = (int64_t)b * H + h;
+            n_cand = flt.cand_cnt[row];
+            // fewer than k kept: the threshold was too high and some of the k best are missing; more than
+            // the list holds: some were dropped.  Either way the head is ranked the ordinary way later.
+            if (flt.fail[row] != 0 || n_cand > flt.cap || n_cand < k_eff) {
+                if (threadIdx.x == 0) {
+                    flag_failed(flt, row);
+                    atomicAdd(flt.n_failed, 1);
+                }
+                return;
+            }
+            src = flt.cand + row * flt.cap;
+        }
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int sl = i * SEL_THREADS + threadIdx.x;
-            const uint64_t cv = my_parts[sl < n_cand ? sl : n_cand - 1];
+            const uint64_t cv = src[sl < n_cand ? sl : n_cand - 1];
             keys[i] = sl < n_cand ? (uint32_t)(cv >> 32) : 0u;
             pos_of[i] = (int)~(uint32_t)cv;
         }
@@ -553,7 +604,12 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
     //    A streamed row keeps the maxima of 8 disjoint groups of the thread's candidates instead
     //    (one instruction per key): distinct candidates again, so the same argument holds, and
     //    with 8192 group maxima the bound is about as tight.
+    //    The candidates a filtered pass kept are few and most of them are among the k best: no bound
+    //    (d0 = 0) and no list for them.
+    const bool direct = MERGE && flt.thr != nullptr;
     constexpr int MG = ITEMS > 0 ? MTOP : ITEMS == -1 ? 4 : 8;
+    uint32_t d0 = 0u;
+    if (!direct) {
     uint32_t top[MG];
 #pragma unroll
     for (int j = 0; j < MG; ++j) top[j] = 0u;
@@ -584,8 +640,9 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
     for (int j = 0; j < MG; ++j) atomicAdd(&hist[top[j] >> 21], 1);
     __syncthreads();
     pick_digit<2048>(hist, scratch, &st, 21);
-    const uint32_t d0 = st.prefix >> 21;
+    d0 = st.prefix >> 21;
     __syncthreads();
+    }
     // 1-3 for candidates delivered by scan_fn: the remaining digits of the k_eff-th best score key
     // T (its top digit is already in st), the position bound among the keys equal to T when they
     // straddle the cut (rare), and the survivors' composites compacted into sort_buf in any order.
@@ -670,7 +727,7 @@ __global__ __launch_bounds__(SEL_THREADS, ITEMS == -1 ? 8 : 4) void topk_kernel(
     });
     __syncthreads();
     pick_digit<2048>(hist, scratch, &st, 21);
-    if constexpr (CAP > 0) {
+    if (CAP > 0 && !direct) {
         int slot = wave_reserve(listable, &n_list);
         __syncthreads();
         listed = n_list <= CAP;
@@ -964,6 +1021,242 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
     if (tid == 0) cnt[b] = n_take + window;
 }
 
+// ---------------------------------------------------------------- filtered selection: the threshold
+//
+// Writing a score for every (head, cached token) is what the selection layer's pass pays most for
+// beyond its reads, and the per-head top-k then walks all of them again.  The fast path of a selection
+// layer writes only the scores that can matter.  A first, small launch (this kernel) scores a SAMPLE
+// of the tokens -- every tile_step-th tile of 64 -- and takes, per head, a threshold theta from the
+// sample such that with overwhelming probability at least k and not many more than k of the head's
+// candidates score >= theta; the pass then keeps only those (as (score key, position) composites,
+// compacted per head) and the top-k ranks among them.  theta is only a guess, so everything that
+// depends on it is checked: a head whose kept candidates turn out fewer than k (theta too high) or more
+// than the buffers hold (theta too low, or many equal scores) is flagged, and the flagged heads are
+// scored and ranked again the ordinary way (score_kernel and topk_kernel in their only_failed forms).
+// The result never depends on theta; only the time does.
+//
+// The sample of a head has n_s candidates out of n (every position in a sampled tile that is a
+// candidate); with the target fraction f = k / n, theta is at or just below the j-th largest of the
+// sample, where
+//   j = f n_s + FILTER_Z sqrt(f (1 - f) n_s) + 1:
+// the number of sample members among the head's true top k is hypergeometric with mean f n_s and
+// standard deviation below sqrt(f (1 - f) n_s), so it exceeds j - 1 with probability ~ 3e-7 at
+// FILTER_Z = 5 for tokens in no particular order (ordered inputs can defeat any fixed sample; they cost
+// the second chance, nothing else).  A head whose expected share of kept candidates is above
+// FILTER_MAX_SHARE, or whose kept candidates would likely overflow its buffer, gains nothing from the
+// filter and is flagged at once.
+//
+// One 1024-thread workgroup per (sequence, KV head).  Every wave scores sampled tiles on its own,
+// straight from memory on the matrix cores (below); the keys of the sample stay in LDS, [head][slot].  Then a quarter of the workgroup works on each
+// head: the sample's scores are counted into 2048 bins that divide [lowest, highest sample score]
+// evenly (by value, not by key: keys are dense where scores are small and a digit of the key would
+// put most of the sample into a handful of bins), the bin that holds the j-th largest is found by a
+// scan from the top, and theta is the smallest sample key in that bin -- so the number of sample
+// members at or above theta is known exactly (j' >= j), and the expected share is j' / (n_s + 1).
+constexpr int SAMPLE_STEP = 16;                       // every 16th tile at least ...
+constexpr int SAMPLE_MAX_TILES = 64;                  // ... and 64 tiles (4096 sample slots) per sequence at most
+constexpr float FILTER_Z = 5.0f;
+constexpr float FILTER_MAX_SHARE = 0.4f;
+constexpr int THR_BINS = 2048;
+
+// Expected number of kept candidates plus three standard deviations, for a head with n candidates,
+// n_s of them sampled, jp sample members at or above the threshold.
+__host__ __device__ inline float filter_kept_bound(float n, float n_s, float jp) {
+    const float share = jp / (n_s + 1.0f);
+    return n * (share + 3.0f * sqrtf(share * (1.0f - share) / (n_s > 1.0f ? n_s : 1.0f)));
+}
+// j of the account above.
+__host__ __device__ inline int filter_sample_rank(float k_eff, float n, float n_s) {
+    const float frac = k_eff / n;
+    return (int)(frac * n_s + FILTER_Z * sqrtf(frac * (1.0f - frac) * n_s)) + 1;
+}
+
+template <int GQ, bool PAGED>
+__global__ __launch_bounds__(SEL_THREADS) void sample_threshold_kernel(const uint16_t* __restrict__ q, int H, int k,
+                                                                        int budget, int window, int tile_step,
+                                                                        int n_slots_max, FilterState f, KvView kv) {
+    static_assert(GQ <= 4, "a quarter of the workgroup per head");
+    extern __shared__ uint32_t thr_lds_buf[];         // keys [GQ][n_slots_max], then bins [GQ][THR_BINS]
+    uint32_t* const keys_all = thr_lds_buf;
+    int* const hist_all = reinterpret_cast<int*>(thr_lds_buf + GQ * n_slots_max);
+    __shared__ uint32_t red_min[4][4], red_max[4][4], thr_min[4];
+    __shared__ int red_cnt[4][4], wave_sum[4][4], sel_bin[4], sel_jp[4];
+    const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row0 = (int64_t)b * H + kvh * GQ;     // first head of the group
+    if (tid < GQ) {
+        f.cand_cnt[row0 + tid] = 0;
+        f.fail[row0 + tid] = 0;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *f.n_failed = 0;   // counted by the top-k, a later launch
+    const int L = kv.seq_lens[b];
+    if (L <= budget) {                                  // rho is every token: nothing is selected
+        if (tid < GQ) f.thr[row0 + tid] = 0xffffffffu;
+        return;
+    }
+    const int Lc = L - window, n = Lc - f.n_sink, k_eff = k < n ? k : n;
+    const int tiles_all = (Lc + 63) >> 6;
+    const int n_tiles = (tiles_all + tile_step - 1) / tile_step;   // sampled tiles: <= n_slots_max / 64
+    const int n_slots = n_tiles * 64;
+
+    // The sample's scores come from V_MFMA_F32_16X16X16_BF16, 16 tokens x 16 heads (GQ of them real) per
+    // instruction: lane l holds, of token l % 16 and of head l % 16, the 16-byte chunks (4 j + l / 16) of
+    // the 128 columns, j = 0 .. 3 -- the order in which columns are summed does not matter here, a sample
+    // score only helps to guess a threshold and need not be the score the pass computes to the last bit.
+    // A load instruction reads 64 contiguous bytes of each of 16 rows.
+    const int m16 = lane & 15, kg = lane >> 4;
+    u32x4 qreg[4];
+#pragma unroll
+    for (int jc = 0; jc < 4; ++jc) {
+        qreg[jc] = u32x4{0u, 0u, 0u, 0u};
+        if (m16 < GQ) qreg[jc] = *reinterpret_cast<const u32x4*>(q + (row0 + m16) * D + (jc * 4 + kg) * 8);
+    }
+    for (int s = wave; s < n_tiles; s += SEL_WAVES) {
+        const int t0 = s * tile_step * 64;
+#pragma unroll
+        for (int pair = 0; pair < 2; ++pair) {
+            u32x4 stage[2][4];
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2) {
+                const int t = t0 + (pair * 2 + g2) * 16 + m16;
+                const uint16_t* __restrict__ krow = kv.k + row_offset<PAGED>(kv, b, kvh, min(t, Lc - 1));
+#pragma unroll
+                for (int jc = 0; jc < 4; ++jc) stage[g2][jc] = *reinterpret_cast<const u32x4*>(krow + (jc * 4 + kg) * 8);
+            }
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2) {
+                f32x4 acc = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int jc = 0; jc < 4; ++jc) {
+                    const s16x4 a_lo = __builtin_bit_cast(s16x4, make_uint2(stage[g2][jc].x, stage[g2][jc].y));
+                    const s16x4 a_hi = __builtin_bit_cast(s16x4, make_uint2(stage[g2][jc].z, stage[g2][jc].w));
+                    const s16x4 b_lo = __builtin_bit_cast(s16x4, make_uint2(qreg[jc].x, qreg[jc].y));
+                    const s16x4 b_hi = __builtin_bit_cast(s16x4, make_uint2(qreg[jc].z, qreg[jc].w));
+                    acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, b_lo, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, b_hi, acc, 0, 0, 0);
+                }
+                // the lane holds, for head l % 16, the tokens 4 (l / 16) + i of this group of 16
+                if (m16 < GQ) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int m = (pair * 2 + g2) * 16 + kg * 4 + i, t = t0 + m;
+                        const bool valid = t < Lc && t >= f.n_sink;   // key 0 for what is no candidate
+                        keys_all[m16 * n_slots_max + s * 64 + m] = valid ? score_key(acc[i]) : 0u;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // a quarter of the workgroup (4 waves) per head; quarters without a head only keep the barriers company
+    const int hq = tid >> 8, tq = tid & 255, wq = tq >> 6;
+    const bool has_head = hq < GQ;
+    const uint32_t* const keys = keys_all + (has_head ? hq : 0) * n_slots_max;
+    int* const hist = hist_all + (has_head ? hq : 0) * THR_BINS;
+    {
+        int cnt = 0;
+        uint32_t lo = 0xffffffffu, hi = 0u;
+        if (has_head) {
+            for (int sl = tq; sl < n_slots; sl += 256) {
+                const uint32_t key = keys[sl];
+                if (key != 0u) {
+                    ++cnt;
+                    lo = key < lo ? key : lo;
+                    hi = key > hi ? key : hi;
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            cnt += __shfl_xor(cnt, o);
+            const uint32_t lo2 = __shfl_xor(lo, o), hi2 = __shfl_xor(hi, o);
+            lo = lo2 < lo ? lo2 : lo;
+            hi = hi2 > hi ? hi2 : hi;
+        }
+        if (lane == 0) {
+            red_cnt[hq][wq] = cnt;
+            red_min[hq][wq] = lo;
+            red_max[hq][wq] = hi;
+        }
+        for (int i = tq; i < THR_BINS; i += 256) hist[i] = 0;
+        if (tq == 0) thr_min[hq] = 0xffffffffu;
+    }
+    __syncthreads();
+    int n_s = 0;
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        n_s += red_cnt[hq][w];
+        kmin = red_min[hq][w] < kmin ? red_min[hq][w] : kmin;
+        kmax = red_max[hq][w] > kmax ? red_max[hq][w] : kmax;
+    }
+    const int j = filter_sample_rank((float)k_eff, (float)n, (float)n_s);
+    const float smin = key_score(kmin), range = key_score(kmax) - smin;
+    // no usable guess: too few in the sample, or scores that are not finite or all alike
+    bool bad = !has_head || j >= n_s || !(range > 0.0f && range < 3.0e38f);
+    const float scale = bad ? 0.0f : (float)(THR_BINS - 1) / range;
+    auto bin_of = [&](uint32_t key) {
+        const int bi = (int)((key_score(key) - smin) * scale);
+        return bi < 0 ? 0 : bi > THR_BINS - 1 ? THR_BINS - 1 : bi;
+    };
+    if (!bad) {
+        for (int sl = tq; sl < n_slots; sl += 256) {
+            const uint32_t key = keys[sl];
+            if (key != 0u) atomicAdd(&hist[bin_of(key)], 1);
+        }
+    }
+    __syncthreads();
+    {   // thread i of the quarter owns the 8 bins [2048 - 8 (i + 1), 2048 - 8 i), walked from the top
+        int local[8], sum = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            local[u] = hist[THR_BINS - 1 - (tq * 8 + u)];
+            sum += local[u];
+        }
+        int inc = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(inc, o);
+            if (lane >= o) inc += up;
+        }
+        if (lane == 63) wave_sum[hq][wq] = inc;
+        __syncthreads();
+        int above = inc - sum;                          // sample members in higher bins, owned by lower threads
+        for (int w = 0; w < wq; ++w) above += wave_sum[hq][w];
+        if (!bad && above < j && j <= above + sum) {
+            int run = above;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (run < j && j <= run + local[u]) {
+                    sel_bin[hq] = THR_BINS - 1 - (tq * 8 + u);
+                    sel_jp[hq] = run + local[u];
+                }
+                run += local[u];
+            }
+        }
+    }
+    __syncthreads();
+    if (!bad) {
+        const int bsel = sel_bin[hq];
+        uint32_t lo = 0xffffffffu;
+        for (int sl = tq; sl < n_slots; sl += 256) {
+            const uint32_t key = keys[sl];
+            if (key != 0u && bin_of(key) == bsel) lo = key < lo ? key : lo;
+        }
+        if (lo != 0xffffffffu) atomicMin(&thr_min[hq], lo);
+    }
+    __syncthreads();
+    if (has_head && tq == 0) {
+        const int64_t row = row0 + hq;
+        if (!bad) {
+            const float jp = (float)sel_jp[hq];
+            bad = jp / (float)(n_s + 1) > FILTER_MAX_SHARE || filter_kept_bound((float)n, (float)n_s, jp) > (float)f.cap;
+        }
+        f.thr[row] = bad ? 0xffffffffu : thr_min[hq];
+        if (bad) flag_failed(f, row);
+    }
+}
+
 // Aggregation for the other two readings of "globally ranked" (Sec. 3.2 names no ranking key):
 // one key per candidate position, larger = better, 0 = proposed by no head.
 //   votes     : (number of proposing heads) << 13 | (8191 - best rank among them)
@@ -1108,7 +1401,6 @@ __host__ __device__ inline int attn_active_splits(int n, int chunk) {
     return a < 1 ? 1 : a;
 }
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -1167,13 +1459,14 @@ __device__ __forceinline__ void wave_lds_sync() {
 // -- the head-to-head selection the paper compares with (Sec. 3.2, the generalization figure) --
 // so a workgroup serves one query head, blockIdx.y counts query heads (G of them) and head y reads
 // KV head y >> hshift.  Nothing is shared inside a GQA group: each head fetches its own rows.
-template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_HEAD = false>
+template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_HEAD = false, bool FILTER = false>
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
     const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
     float* __restrict__ part_acc, float* __restrict__ part_ml, uint16_t* __restrict__ out, float* __restrict__ lse,
-    float* __restrict__ P, int64_t ldp, int window, int hshift, KvView kv) {
+    float* __restrict__ P, int64_t ldp, int window, int hshift, FilterState flt, KvView kv) {
     static_assert(!(SCORE && SPARSE), "scores are emitted by the pass over all tokens");
+    static_assert(!FILTER || SCORE, "the filter is a form of the scoring variant");
     static_assert(!PER_HEAD || (SPARSE && GQ == 1), "per-head token lists: one query head per workgroup");
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
@@ -1211,6 +1504,14 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr int STAGE_TOK = GQ >= 8 ? ATTN_SCORE_CHUNK_CAP_G8 : ATTN_SCORE_CHUNK_CAP;   // 32 KB at groups of 4 and 8
     constexpr int STAGE_IT = STAGE_TOK / WG_TILE;
     __shared__ __attribute__((aligned(16))) float pstage[SCORE ? GQ * STAGE_TOK : 4];
+    // Filtered form of the scoring variant (FILTER; see sample_threshold_kernel): instead of every score,
+    // the buffer takes the (score key, position) composites of the candidates at or above the head's
+    // threshold, compacted per head -- STAGE_CAND of them per head at most, or the head is flagged.
+    constexpr int STAGE_CAND = STAGE_TOK / 2;         // composites are twice a score's size
+    uint64_t* const cstage = reinterpret_cast<uint64_t*>(pstage);
+    __shared__ int cand_n[SCORE ? GQ : 1], cand_base[SCORE ? GQ : 1];
+    __shared__ uint32_t thr_lds[SCORE ? GQ : 1];
+    constexpr bool filtered = FILTER;
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
@@ -1289,7 +1590,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr bool PREFETCH = !SCORE;
     // The scoring variant of a group of 8 has no registers for K and V rows at once (64 each at 64-token
     // tiles, beside 64 accumulators): its V rows are requested once the K rows are parked in LDS.
-    constexpr bool V_LATE = SCORE && GQ >= 8;
+    constexpr bool V_LATE = SCORE && (GQ >= 8 || (FILTER && GQ >= 4));
     u32x4 kreg[TI], vreg[TI];
     int64_t off[TI];
     // a valid position for row load i of the tile that starts at list entry t_ (an index outside the
@@ -1364,6 +1665,53 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             }
         }
     };
+    // filtered form: the staged candidates of every head go to the head's list in memory, one reservation
+    // per head and workgroup.  The reservation is a device-scope atomic whose answer takes microseconds:
+    // reserve_candidates asks (thread h for head h; returns the answer, -1 if there is nothing to copy),
+    // copy_candidates uses the answer and empties the buffer -- at the end of a run the workgroup merges
+    // and writes its attention partials in between.  Both are called by the whole workgroup.
+    auto reserve_candidates = [&]() -> int {
+        int base = -1;
+        if constexpr (SCORE) {
+            lds_barrier();                               // every wave's candidates are staged
+            if (tid < GQ) {
+                const int n_h = cand_n[tid];
+                if (n_h > STAGE_CAND) flag_failed(flt, head0 + tid);   // more candidates than the buffer held: some are lost
+                else if (n_h > 0) base = atomicAdd(&flt.cand_cnt[head0 + tid], n_h);
+            }
+        }
+        return base;
+    };
+    auto copy_candidates = [&](int base) {
+        if constexpr (SCORE) {
+            if (tid < GQ) {
+                if (base >= 0 && base + cand_n[tid] > flt.cap) {   // the head's list is full (the count stays above cap: the ranking sees it too)
+                    flag_failed(flt, head0 + tid);
+                    base = -1;
+                }
+                cand_base[tid] = base;
+            }
+            lds_barrier();
+#pragma unroll
+            for (int h = 0; h < GQ; ++h) {
+                const int n_h = cand_n[h], base_h = cand_base[h];
+                if (base_h >= 0) {
+                    uint64_t* const dst = flt.cand + (head0 + h) * flt.cap + base_h;
+                    for (int i = tid; i < n_h; i += ATTN_THREADS) dst[i] = cstage[h * STAGE_CAND + i];
+                }
+            }
+            lds_barrier();                               // all read, before the counters start again
+            if (tid < GQ) cand_n[tid] = 0;
+            lds_barrier();
+        }
+    };
+    if constexpr (FILTER) {                              // the heads' thresholds wait in LDS, not in registers
+        if (tid < GQ) {
+            thr_lds[tid] = flt.thr[head0 + tid];
+            cand_n[tid] = 0;
+        }
+        lds_barrier();
+    }
     int t_opaque = 0;                                    // always zero, unknown to the compiler
     int it_staged = 0;                                   // first iteration whose scores are still in the staging buffer
     int it = 0;                                          // iterations of the workgroup so far
@@ -1375,9 +1723,13 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         // workgroup-uniform; the buffer holds STAGE_IT iterations at most
         const bool burst_due = SCORE && it - it_staged == STAGE_IT;
         if (burst_due) {
-            lds_barrier();                               // every wave's scores since the last burst are staged
-            flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
-            lds_barrier();                               // ... and read, before the buffer is written again
+            if (filtered) {
+                copy_candidates(reserve_candidates());
+            } else {
+                lds_barrier();                           // every wave's scores since the last burst are staged
+                flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
+                lds_barrier();                           // ... and read, before the buffer is written again
+            }
             it_staged = it;
         }
         if (!active) {
@@ -1479,7 +1831,24 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
                             sc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], sc[s], 0, 0, 0);
                 }
             }
-            if (lane < TILE) {
+            if (filtered) {
+                const int t = t0 + tl;
+                const bool is_cand = lane < TILE && t >= flt.n_sink && t < min(end, L - window);
+#pragma unroll
+                for (int h = 0; h < GQ; ++h) {
+                    const uint32_t key = score_key(sc[h >> 2][h & 3]), thr = thr_lds[h];
+                    const bool keep = is_cand && thr != 0xffffffffu && key >= thr;
+                    const uint64_t kept = __ballot(keep);
+                    if (kept) {                          // wave-uniform: one reservation per wave and head
+                        int base = 0;
+                        if (lane == 0) base = atomicAdd(&cand_n[h], __popcll(kept));
+                        base = __builtin_amdgcn_readfirstlane(base);
+                        const int slot = base + mbcnt(kept);
+                        if (keep && slot < STAGE_CAND) cstage[h * STAGE_CAND + slot] = ((uint64_t)key << 32) | (uint32_t)~(uint32_t)t;
+                    }
+                    asm volatile("" ::: "memory");       // one head at a time: nothing of the next is fetched early
+                }
+            } else if (lane < TILE) {
 #pragma unroll
                 for (int h = 0; h < GQ; ++h) pstage[h * STAGE_TOK + (it - it_staged) * WG_TILE + wave * TILE + tl] = sc[h >> 2][h & 3];
             }
@@ -1552,8 +1921,11 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         }
         wave_lds_sync();                              // the tile buffers are rewritten next iteration
     }
+    int cand_reserved = -1;
     if constexpr (SCORE) {
-        if (it > it_staged) {                          // the iterations staged since the last burst
+        if (filtered) {
+            cand_reserved = reserve_candidates();        // used after the merge below
+        } else if (it > it_staged) {                   // the iterations staged since the last burst
             lds_barrier();
             flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
         }
@@ -1622,6 +1994,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             }
         }
     }
+    if constexpr (FILTER) copy_candidates(cand_reserved);
 }
 
 // Merge of the split-K partials of sequences that kept more than one workgroup busy.

@@ -39,11 +39,14 @@ class StepRunner:
         self.idx = torch.full((w.batch, w.budget), -1, dtype=torch.int32, device=dev)
         self.cnt = torch.zeros((w.batch,), dtype=torch.int32, device=dev)
         self.ws = cb.alloc_workspace(self.params, self.max_len, dev)
+        self.scores_valid = False     # whether the workspace holds the selection scores of the last call
         self.step = cb.DecodeStep(self.params, self.schedule, [l.q for l in inp.layers], self.kvs, self.outs,
                                   self.idx, self.cnt, self.ws)
 
     def run(self):
         self.step.run()
+        # a selection layer on the filtered fast path writes no score array
+        self.scores_valid = not self.filtered_select()
 
     def grow(self, n: int = 1):
         """Every sequence gets n more tokens (already present in the drawn caches), as after n decode steps."""
@@ -54,10 +57,12 @@ class StepRunner:
     # single entry points on one layer (by position in inp.layers)
     def select(self, layer_pos: int):
         cb.select(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt, self.ws)
+        self.scores_valid = True
 
     def select_layer(self, layer_pos: int):
         cb.select_layer(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.idx,
                         self.cnt, self.ws)
+        self.scores_valid = not self.filtered_select()
 
     def sparse(self, layer_pos: int):
         cb.sparse_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.idx, self.cnt,
@@ -85,6 +90,10 @@ class StepRunner:
 
     def full(self, layer_pos: int):
         cb.full_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.ws)
+
+    def filtered_select(self) -> bool:
+        """Whether a selection layer of this size keeps candidates instead of writing the score array."""
+        return bool(cb.workspace_layout(self.params, self.max_len).filtered_select)
 
     # selection intermediates, for parity tests
     def scores(self) -> torch.Tensor:

@@ -144,6 +144,21 @@ def test_workspace_bytes_never_shrink_with_capacity(B, H, G, K, W):
         prev = n
 
 
+def test_layout_reports_the_filtered_fast_path():
+    """The layout says whether a selection layer of this size keeps only the scores that can matter: many scores,
+    groups of at most four heads, the default ranking, a sample dense enough for the longest sequence."""
+    c5 = dict(batch=64, n_q_heads=32, n_kv_heads=8, budget=2048, window=512)
+    assert cb.workspace_layout(cb.make_params(**c5), 32768).filtered_select == 1
+    assert cb.workspace_layout(cb.make_params(**c5), 8192).filtered_select == 1
+    assert cb.workspace_layout(cb.make_params(**c5), 4096).filtered_select == 0          # few scores, k a large share
+    assert cb.workspace_layout(cb.make_params(**dict(c5, batch=1)), 32768).filtered_select == 0
+    assert cb.workspace_layout(cb.make_params(**dict(c5, n_q_heads=64)), 32768).filtered_select == 0   # groups of 8
+    assert cb.workspace_layout(cb.make_params(**dict(c5, rank_mode=cb.RANK_VOTES)), 32768).filtered_select == 0
+    # a bound so long that the 64 sampled tiles are too thin a sample for k = 1536: the ordinary way, same buffers
+    far = cb.workspace_layout(cb.make_params(**c5), 1 << 20)
+    assert far.filtered_select == 0 and far.total_bytes >= cb.workspace_bytes(cb.make_params(**c5), 32768)
+
+
 def test_build_id_matches_the_sources():
     from paper_2508_07101_amd import build
     assert cb.load().cusa_build_id().decode() == build.source_id() == cb.built_from()

@@ -42,7 +42,7 @@ def check_select(inp, runner, layer_pos, seqs=None, check_scores=True, rank_mode
                                          n_sink=w.n_sink)
         if L > w.budget:
             Lc = L - w.window
-            if check_scores:
+            if check_scores and runner.scores_valid:
                 got = P_dev[b, :, :Lc].cpu().numpy()
                 assert (got.view(np.uint32) == P.view(np.uint32)).all(), f"scores differ, seq {b}"
             k_eff = rho_head.shape[1]
@@ -73,7 +73,12 @@ def run_and_check(w, layers=None, seqs=None, check_scores=True):
     r.run()
     torch.cuda.synchronize()
     sel = max(i for i, k in enumerate(sched) if k == LAYER_SELECT)
+    # a selection layer on the filtered fast path writes no score array: the scores are then checked on cusa_select's
     check_select(inp, r, sel, seqs, check_scores)
+    if check_scores and r.filtered_select():
+        _say(f"{w.name}: filtered selection layer; scores from cusa_select")
+        r.select(sel)
+        check_select(inp, r, sel, seqs, True)
     return inp, r, sched
 
 
@@ -520,6 +525,55 @@ def test_few_long_ragged_rows_are_ranked_in_slices(mode):
     _with_keys(w, dup, rank_mode=mode)
 
 
+def _kernel_calls(fn):
+    cb.profile_reset()
+    cb.profile_enable(True)
+    fn()
+    torch.cuda.synchronize()
+    prof = cb.profile_read()
+    cb.profile_enable(False)
+    return {k: v["calls"] for k, v in prof.items()}
+
+
+def test_filtered_selection_layer_fast_path_and_its_second_chance():
+    """A selection layer with many scores keeps only the candidates above a sampled threshold.  The result must
+    not depend on the guess: random scores (the guess holds), massive ties (far more candidates than the lists
+    hold), and a sequence whose large scores all sit where the sample does not look (fewer candidates than k)."""
+    lens = (18000, 9000, 17011, 12345, 16000, 15999, 9777, 18000, 11000, 13579, 10001, 17500, 14000, 9100, 16384, 12800)
+    w = small("filter", batch=16, seq_len=18000, lengths=lens, budget=2048, window=512, n_planted=9)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    assert r.filtered_select()
+    calls = _kernel_calls(r.run)
+    assert calls["sample_threshold_kernel"] == 1 and calls["topk_kernel<filtered>"] == 1
+    check_select(inp, r, 0, check_scores=False)
+    for i, kind in enumerate(w.schedule):
+        check_attention(inp, r, i, kind, seqs=[0, 7])
+    # massive ties: most keys zero -> most scores exactly 0 and equal
+    k = inp.layers[0].k
+    saved = k.clone()
+    k.copy_(torch.sign(k) * (k.abs() > 1.5))
+    r.run()
+    check_select(inp, r, 0, check_scores=False)
+    # Where the sample does not look.  Sequence 3: every key OUTSIDE the sampled tiles is made to score high, so the
+    # threshold (from ordinary scores) lets nearly everything through: more candidates than the buffers hold.
+    # Sequence 5: only the keys INSIDE the sampled tiles score high, so the threshold is far too high and fewer
+    # than k candidates pass.  Both heads' worth are found out and ranked again the ordinary way.
+    k.copy_(saved)
+    q = inp.layers[0].q
+    for b, inside in ((3, False), (5, True)):
+        Lb = inp.seq_lens_host[b]
+        pos = torch.arange(Lb, device=k.device)
+        sampled = (pos // 64) % 16 == 0                                               # the library samples every 16th tile of 64 tokens at this length
+        chosen = sampled if inside else ~sampled
+        boost = 4.0 * q[b].float().view(8, 4, 128).mean(dim=1)                        # [G, d], along the group's queries
+        rows = k[b, :, :Lb][:, chosen].float() * 0.05 + boost[:, None, :]
+        k[b, :, torch.nonzero(chosen).squeeze(1)] = rows.to(torch.bfloat16)
+    r.run()
+    check_select(inp, r, 0, check_scores=False)
+    check_attention(inp, r, 1, LAYER_SPARSE, seqs=[3, 5])
+
+
 def test_many_rows_take_the_lean_streamed_topk():
     """512 rows of more than 8192 candidates: the per-head top-k runs its register-lean streamed form, two rows
     at a time per CU (ragged lengths, so that rows end inside a batch of keys)."""
@@ -597,7 +651,8 @@ def test_c5_full_size_whole_step_every_sequence():
     r = StepRunner(inp)
     _say(f"c5: whole step, {len(inp.layers)} layers; attention on sequences {seqs}")
     r.run()
-    check_select(inp, r, 0)                              # every sequence
+    assert r.filtered_select()                           # the step's selection layer takes the filtered fast path here
+    check_select(inp, r, 0, check_scores=False)          # every sequence
     _say("c5: selection equal to the oracle's for all sequences")
     check_attention(inp, r, 0, LAYER_FULL, seqs[:1])
     check_attention(inp, r, 1, LAYER_SPARSE, seqs)
