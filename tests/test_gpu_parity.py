@@ -574,6 +574,26 @@ def test_filtered_selection_layer_fast_path_and_its_second_chance():
     check_attention(inp, r, 1, LAYER_SPARSE, seqs=[3, 5])
 
 
+@pytest.mark.parametrize("H,paged,sinks,k", [(8, True, 4, 0), (16, False, 0, 0), (32, True, 40, 2048)])
+def test_filtered_selection_layer_group_sizes_layouts_sinks(H, paged, sinks, k):
+    """The fast path for query groups of 1, 2 and 4 heads, both cache layouts, with sinks, and with a per-head k
+    above K - W; ragged lengths, one sequence within the budget."""
+    B = 32 * 32 // H if H < 32 else 28
+    rng = np.random.default_rng(H)
+    lens = [int(x) for x in rng.integers(9000, 11000, size=B)]
+    lens[1], lens[2] = 11000, 300
+    w = small(f"filter_g{H // 8}", batch=B, n_q_heads=H, seq_len=11000, lengths=tuple(lens), budget=1024, window=256,
+              paged=paged, n_sink=sinks, topk_per_head=k, n_planted=6)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp)
+    assert r.filtered_select()
+    calls = _kernel_calls(r.run)
+    assert calls["sample_threshold_kernel"] == 1 and calls["topk_kernel<filtered>"] == 1
+    check_select(inp, r, 0, seqs=range(0, B, 3), check_scores=False)
+    check_attention(inp, r, 0, LAYER_SELECT, seqs=[1, 2])
+    check_attention(inp, r, 1, LAYER_SPARSE, seqs=[0, 2])
+
+
 def test_many_rows_take_the_lean_streamed_topk():
     """512 rows of more than 8192 candidates: the per-head top-k runs its register-lean streamed form, two rows
     at a time per CU (ragged lengths, so that rows end inside a batch of keys)."""
