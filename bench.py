@@ -403,7 +403,7 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
                 k["frac_of_hbm_peak"] = round(k["achieved_GBs"] / HBM_PEAK_GBS, 4)
             kernels[kname] = k
         for kname in BANDWIDTH_KERNELS:
-            if kname in kernels:
+            if kname in kernels and "achieved_GBs" in kernels[kname]:
                 k = kernels[kname]
                 # traffic: HBM bytes per launch from rocprofv3 counters, where a summary of them is committed
                 rooflines.append({"kernel": kname, "bound": "hbm", "achieved": k["achieved_GBs"], "peak": HBM_PEAK_GBS,

@@ -1095,7 +1095,8 @@ __global__ __launch_bounds__(SEL_THREADS) void sample_threshold_kernel(const uin
     }
     const int Lc = L - window, n = Lc - f.n_sink, k_eff = k < n ? k : n;
     const int tiles_all = (Lc + 63) >> 6;
-    const int n_tiles = (tiles_all + tile_step - 1) / tile_step;   // sampled tiles: <= n_slots_max / 64
+    // sampled tiles: <= n_slots_max / 64 for every sequence within the bound the launch was planned for
+    const int n_tiles = min((tiles_all + tile_step - 1) / tile_step, n_slots_max >> 6);
     const int n_slots = n_tiles * 64;
 
     // The sample's scores come from V_MFMA_F32_16X16X16_BF16, 16 tokens x 16 heads (GQ of them real) per
