@@ -801,13 +801,21 @@ def test_random_small_configurations():
                 assert_close_bf16(out[b], oracle.attention_per_head(q, Kc, Vc, rho_h), f"case {case}: per-head attention seq {b}")
 
 
-def test_decode_step_captured_in_a_hip_graph_replays_like_the_eager_step():
+@pytest.mark.parametrize("filtered", [False, True])
+def test_decode_step_captured_in_a_hip_graph_replays_like_the_eager_step(filtered):
     """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a step can be
-    captured once and replayed; every replay must give what the eager step gives."""
-    w = small("graph", n_layers=4, schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SPARSE), batch=3,
-              seq_len=2600, lengths=(2600, 140, 1777), paged=True, n_planted=4, n_sink=4)
+    captured once and replayed; every replay must give what the eager step gives -- whatever the workspace
+    holds when it starts (it is scribbled over between the replays), also on the filtered selection, whose
+    counters and flags live there."""
+    if filtered:
+        w = small("graphf", n_layers=3, schedule=(LAYER_SELECT, LAYER_SPARSE, LAYER_SPARSE), batch=20, seq_len=14000,
+                  min_seq_len=12000, budget=1024, window=256, paged=True, n_planted=4, n_sink=4)
+    else:
+        w = small("graph", n_layers=4, schedule=(LAYER_FULL, LAYER_SELECT, LAYER_SPARSE, LAYER_SPARSE), batch=3,
+                  seq_len=2600, lengths=(2600, 140, 1777), paged=True, n_planted=4, n_sink=4)
     inp = wl.make_inputs(w, DEV)
     r = StepRunner(inp)
+    assert r.filtered_select() == filtered
     r.run()                                            # eager: also warms the library (LDS attributes) before capture
     torch.cuda.synchronize()
     want_idx, want_outs = r.idx.clone(), [o.clone() for o in r.outs]
@@ -816,6 +824,7 @@ def test_decode_step_captured_in_a_hip_graph_replays_like_the_eager_step():
         r.run()
     for replay in range(3):
         r.idx.fill_(-1)                                # eager work between the replays
+        r.ws.fill_(0xA5 if replay % 2 else 0)
         for o in r.outs:
             o.zero_()
         torch.cuda.synchronize()
