@@ -288,7 +288,8 @@ def cpu_baseline(inp, w, sched, single_thread_too=False):
 
 def traffic_probes(torch, cb):
     """What the memory system gives the access patterns of the attention kernels without their arithmetic
-    (4 GiB each, far beyond the 256 MB last-level cache): a plain streaming read; 256-byte rows gathered with
+    (4 GiB each, far beyond the 256 MB last-level cache): a plain streaming read (grid-stride, and in the 32 KiB
+    tiles per wave the other probes use); 256-byte rows gathered with
     irregular gaps (sparse attention); a streaming read with 1/32 of its volume written back as scattered
     256-byte runs, and with the same volume written in workgroup bursts (the selection layer's pass, which
     stores the scores)."""
@@ -298,6 +299,7 @@ def traffic_probes(torch, cb):
     dst = torch.zeros((n >> 5) + (1 << 20), dtype=torch.uint8, device="cuda:0")
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     runs = {"stream_read": (lambda: cb.probe_stream_read(src, sink), "probe_stream_read_kernel", n),
+            "stream_read_in_tiles": (lambda: cb.probe_traffic(0, src, dst), "probe_traffic_kernel<stream>", n),
             "gathered_rows_read": (lambda: cb.probe_traffic(1, src, dst), "probe_traffic_kernel<gather>", n >> 2),
             "stream_read_with_scattered_writes": (lambda: cb.probe_traffic(2, src, dst), "probe_traffic_kernel<scattered writes>", n),
             "stream_read_with_burst_writes": (lambda: cb.probe_traffic(3, src, dst), "probe_traffic_kernel<burst writes>", n)}

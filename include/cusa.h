@@ -260,13 +260,14 @@ cusa_status cusa_probe_stream_read(const void* src, size_t bytes, void* sink, vo
 
 /* Traffic probes (benchmark support): one kernel with the memory access pattern of an attention
  * kernel and none of its arithmetic; a wave reads 32 KiB tiles with 32 loads of 16 bytes per lane
- * in flight.  pattern 1: the tiles are 256-byte rows gathered, ascending with irregular gaps, from a
+ * in flight (streaming loads, as the attention kernels use for K and V).  pattern 0: nothing else, a
+ * plain streaming read of `bytes`.  pattern 1: the tiles are 256-byte rows gathered, ascending with irregular gaps, from a
  * region four times their size (what sparse attention reads; bytes / 4 are read).  pattern 2:
  * streams `bytes` and writes 1/32 of that volume as 256-byte runs right away (a scoring pass that
  * stores every tile's scores).  pattern 3: streams `bytes` and writes the same volume in workgroup
  * bursts of 32 KiB.  src: device, 16-byte aligned, `bytes` (at least 1 MiB; 4 MiB for pattern 1;
  * whole MiB are used).  dst: device, 16-byte aligned, at least bytes / 32 + 512 KiB for patterns 2
- * and 3 (16 bytes for pattern 1).  Timed through the profiling facility (kernels
+ * and 3 (16 bytes for patterns 0 and 1).  Timed through the profiling facility (kernels
  * "probe_traffic_kernel<...>").  Errors: INVALID_ARG, LAUNCH. */
 cusa_status cusa_probe_traffic(int32_t pattern, const void* src, size_t bytes, void* dst, size_t dst_bytes,
                                void* stream);

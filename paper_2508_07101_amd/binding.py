@@ -281,7 +281,7 @@ def probe_stream_read(src: torch.Tensor, sink: torch.Tensor):
 
 
 def probe_traffic(pattern: int, src: torch.Tensor, dst: torch.Tensor):
-    """Enqueue a traffic probe (1 gathered rows, 2 stream + scattered writes, 3 stream + burst writes)."""
+    """Enqueue a traffic probe (0 stream in tiles, 1 gathered rows, 2 stream + scattered writes, 3 stream + burst writes)."""
     _check(load().cusa_probe_traffic(pattern, _ptr(src), src.numel() * src.element_size(), _ptr(dst),
                                      dst.numel() * dst.element_size(), _stream()), "cusa_probe_traffic")
 

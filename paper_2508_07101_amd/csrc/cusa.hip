@@ -19,13 +19,13 @@ namespace {
 
 // ------------------------------------------------------------------ profiling
 
-enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_PROBE_GATHER, KID_PROBE_RW_SCATTER, KID_PROBE_RW_BURST, KID_SAMPLE_THRESHOLD, KID_TOPK_FILTERED, KID_COUNT };
+enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_PROBE_GATHER, KID_PROBE_RW_SCATTER, KID_PROBE_RW_BURST, KID_SAMPLE_THRESHOLD, KID_TOPK_FILTERED, KID_PROBE_TILES, KID_COUNT };
 const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
                                              "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel", "topk_kernel<slice>",
                                              "topk_kernel<merge>", "probe_traffic_kernel<gather>", "probe_traffic_kernel<scattered writes>",
-                                             "probe_traffic_kernel<burst writes>", "sample_threshold_kernel", "topk_kernel<filtered>"};
+                                             "probe_traffic_kernel<burst writes>", "sample_threshold_kernel", "topk_kernel<filtered>", "probe_traffic_kernel<stream>"};
 
 // With the profiler on, every launch carries a start and a stop event that the runtime fills
 // from the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), which is what a
@@ -858,19 +858,20 @@ cusa_status cusa_probe_stream_read(const void* src, size_t bytes, void* sink, vo
 }
 
 cusa_status cusa_probe_traffic(int32_t pattern, const void* src, size_t bytes, void* dst, size_t dst_bytes, void* stream) {
-    if (pattern < 1 || pattern > 3 || !src || !dst || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return CUSA_ERR_INVALID_ARG;
+    if (pattern < 0 || pattern > 3 || !src || !dst || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return CUSA_ERR_INVALID_ARG;
     const size_t chunk_bytes = (size_t)PROBE_CHUNK_TILES * 32768;             // 1 MiB read per chunk
     // the gathered tiles come from a region four times their size
     const int64_t n_chunks = (int64_t)(bytes / (pattern == 1 ? 4 * chunk_bytes : chunk_bytes));
     if (n_chunks < 1) return CUSA_ERR_INVALID_ARG;
     // results: 1 KiB per tile, in groups of 512 tiles (four rows of 32768 floats) resp. 16 chunks
-    const size_t need = pattern == 1 ? 16 : (size_t)((n_chunks + 15) / 16) * 16 * PROBE_CHUNK_TILES * 1024;
+    const size_t need = pattern <= 1 ? 16 : (size_t)((n_chunks + 15) / 16) * 16 * PROBE_CHUNK_TILES * 1024;
     if (dst_bytes < need) return CUSA_ERR_INVALID_ARG;
     const dim3 grid((unsigned)(n_chunks < 512 ? n_chunks : 512));              // two workgroups per CU
     hipStream_t s = static_cast<hipStream_t>(stream);
     const u32x4* sp = static_cast<const u32x4*>(src);
     float* dp = static_cast<float*>(dst);
-    if (pattern == 1) launch(KID_PROBE_GATHER, probe_traffic_kernel<1>, grid, 256, 0, s, sp, dp, n_chunks);
+    if (pattern == 0) launch(KID_PROBE_TILES, probe_traffic_kernel<0>, grid, 256, 0, s, sp, dp, n_chunks);
+    else if (pattern == 1) launch(KID_PROBE_GATHER, probe_traffic_kernel<1>, grid, 256, 0, s, sp, dp, n_chunks);
     else if (pattern == 2) launch(KID_PROBE_RW_SCATTER, probe_traffic_kernel<2>, grid, 256, 0, s, sp, dp, n_chunks);
     else launch(KID_PROBE_RW_BURST, probe_traffic_kernel<3>, grid, 256, 0, s, sp, dp, n_chunks);
     return launch_status();

@@ -176,7 +176,7 @@ def test_probe_rejects_bad_arguments():
 def test_traffic_probe_rejects_bad_arguments():
     lib = cb.load()
     fake = ctypes.c_void_p(0x10000)
-    assert lib.cusa_probe_traffic(0, fake, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG      # no such pattern
+    assert lib.cusa_probe_traffic(-1, fake, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG     # no such pattern
     assert lib.cusa_probe_traffic(4, fake, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_probe_traffic(2, None, 1 << 22, fake, 1 << 20, None) == cb.ERR_INVALID_ARG
     assert lib.cusa_probe_traffic(2, fake, 1 << 19, fake, 1 << 20, None) == cb.ERR_INVALID_ARG      # under one chunk
