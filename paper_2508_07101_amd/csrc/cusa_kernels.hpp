@@ -52,6 +52,13 @@ __device__ __forceinline__ u32x4 stream_load(const uint16_t* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
 
+// With per-head token lists the heads of a group ask for many of the same rows from different
+// workgroups: those loads stay ordinary, so that the second asker finds the row in L2.
+template <bool SHARED_ROWS>
+__device__ __forceinline__ u32x4 row_load(const uint16_t* p) {
+    return SHARED_ROWS ? *reinterpret_cast<const u32x4*>(p) : stream_load(p);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -1633,7 +1640,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     };
     auto request_k = [&]() {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) kreg[i] = stream_load(kv.k + off[i]);
+        for (int i = 0; i < TI; ++i) kreg[i] = row_load<PER_HEAD>(kv.k + off[i]);
     };
     // After the rows of the tile at t_ have been requested: the lookups for the tile after it.
     auto advance = [&](int t_) {
@@ -1754,7 +1761,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
         }
         if constexpr (!V_LATE) {
 #pragma unroll
-            for (int i = 0; i < TI; ++i) vreg[i] = stream_load(kv.v + off[i]);
+            for (int i = 0; i < TI; ++i) vreg[i] = row_load<PER_HEAD>(kv.v + off[i]);
         }
         if constexpr (!PREFETCH && !V_LATE) advance(t0);
         __builtin_amdgcn_sched_barrier(0);               // keep every load above the arithmetic
@@ -1812,7 +1819,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
                         asm volatile("" : "+v"(t_opaque));
                         make_off(t0 + t_opaque, posA, pgA);
 #pragma unroll
-                        for (int i = 0; i < TI; ++i) vreg[i] = stream_load(kv.v + off[i]);
+                        for (int i = 0; i < TI; ++i) vreg[i] = row_load<PER_HEAD>(kv.v + off[i]);
                         advance(t0);
                         __builtin_amdgcn_sched_barrier(0);
                     }
