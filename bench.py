@@ -44,7 +44,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 QUOTED = ["c1", "c2", "c3", "c4", "c5"]
-BANDWIDTH_KERNELS = ("attn_kernel<sparse>", "attn_kernel<full+score>", "attn_kernel<full>", "score_kernel")
+BANDWIDTH_KERNELS = ("attn_kernel<sparse>", "attn_kernel<full+score>", "attn_kernel<full>", "attn_kernel<scores only>")
 
 
 def parse():
@@ -109,7 +109,7 @@ def kernel_bytes(w, lens, acc):
     return {
         "attn_kernel<full>": sum(acc.full_attn_bytes(G, L) for L in lens),
         "attn_kernel<sparse>": sum(acc.sparse_attn_bytes(G, K, L) for L in lens),
-        "score_kernel": sum(acc.score_bytes(G, L, K, W) for L in lens),
+        "attn_kernel<scores only>": sum(acc.score_bytes(G, L, K, W) for L in lens),
         # the selection layer's pass: K and V once, the scores come from the same K rows
         "attn_kernel<full+score>": sum(acc.full_attn_bytes(G, L) for L in lens),
     }
@@ -388,7 +388,7 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
         kb = kernel_bytes(w, lens, acc)
         tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
         counted = json.load(open(tpath)).get("hbm_bytes_per_launch", {}) if os.path.exists(tpath) else {}
-        # A selection layer on the filtered fast path launches score_kernel and topk_kernel only as the second
+        # A selection layer on the filtered fast path launches the scores-only pass and topk_kernel only as the second
         # chance of heads whose threshold failed; with none flagged they exit at once and move no bytes.
         fast_path = args.entry == "step" and prof.get("sample_threshold_kernel", {}).get("calls", 0) > 0
         for kname, p in prof.items():
@@ -397,7 +397,7 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
             avg_us = p["total_ms"] * 1e3 / p["calls"]
             k = {"launches_per_step": p["calls"] // steps, "avg_us": round(avg_us, 3),
                  "us_per_step": round(p["total_ms"] * 1e3 / steps, 3)}
-            if fast_path and kname in ("score_kernel", "topk_kernel"):
+            if fast_path and kname in ("attn_kernel<scores only>", "topk_kernel"):
                 k["role"] = "second chance of the filtered selection (exits at once when no head is flagged)"
             elif kname in kb and kb[kname] > 0:
                 k["bytes_per_launch"] = kb[kname]

@@ -20,7 +20,7 @@ namespace {
 // ------------------------------------------------------------------ profiling
 
 enum KernelId { KID_SCORE = 0, KID_TOPK, KID_UNION, KID_ATTN_FULL, KID_ATTN_SPARSE, KID_REDUCE, KID_ATTN_SELECT, KID_ATTN_PER_HEAD, KID_RHO_PER_HEAD, KID_RANK_AGG, KID_RECALL, KID_PROBE, KID_TOPK_SLICE, KID_TOPK_MERGE, KID_PROBE_GATHER, KID_PROBE_RW_SCATTER, KID_PROBE_RW_BURST, KID_SAMPLE_THRESHOLD, KID_TOPK_FILTERED, KID_PROBE_TILES, KID_COUNT };
-const char* const kKernelNames[KID_COUNT] = {"score_kernel", "topk_kernel", "union_kernel",
+const char* const kKernelNames[KID_COUNT] = {"attn_kernel<scores only>", "topk_kernel", "union_kernel",
                                              "attn_kernel<full>", "attn_kernel<sparse>", "attn_reduce_kernel",
                                              "attn_kernel<full+score>", "attn_kernel<per-head>", "per_head_rho_kernel",
                                              "rank_aggregate_kernel", "recall_kernel", "probe_stream_read_kernel", "topk_kernel<slice>",
@@ -155,7 +155,6 @@ KvView make_view(const cusa_params* p, const cusa_kv* kv) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-constexpr int SCORE_GRID = 512;    // persistent scoring workgroups: 2 per CU on 256 CUs
 constexpr int MAX_SPLITS = 256;
 constexpr int TARGET_WGS = 512;     // two resident workgroups per CU
 constexpr int CHUNK_CAP = 2048;
@@ -615,37 +614,55 @@ cusa_status run_topk(int lc_max, int B, int H, hipStream_t s, const float* P, in
     return launch_topk<16, true>(a);
 }
 
-template <int GQ>
-void launch_score(bool paged, int grid, hipStream_t s, const KvView& view, const uint16_t* qf, float* P, int64_t ldp,
-                  int H, int budget, int window, int tiles_per_seq, int n_tiles, const int32_t* only_failed,
-                  const int32_t* n_failed) {
-    if (paged)
-        launch(KID_SCORE, score_kernel<GQ, true>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles,
-               only_failed, n_failed, view);
+// P = q.K^T over the candidate range: the selection pass in its scores-only form (no V rows, no output).
+// only_failed / n_failed: the second chance of the filtered selection scores the flagged heads' groups only.
+template <int GQ, int TI>
+void launch_scores_only(const AttnArgs& a) {
+    if (a.paged)
+        launch(KID_SCORE, attn_kernel<GQ, TI, false, true, true, false, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens,
+               a.q, a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0,
+               a.score.filter, a.view);
     else
-        launch(KID_SCORE, score_kernel<GQ, false>, grid, 64 * SCORE_WAVES, 0, s, qf, P, ldp, H, budget, window, tiles_per_seq, n_tiles,
-               only_failed, n_failed, view);
+        launch(KID_SCORE, attn_kernel<GQ, TI, false, false, true, false, false, true>, a.grid, ATTN_THREADS, 0, a.s, a.idx, a.cnt, a.view.seq_lens,
+               a.q, a.budget, a.n_splits, a.chunk, a.view.G, a.scale, a.pa, a.pm, a.out, a.lse, a.score.P, a.score.ldp, a.score.window, 0,
+               a.score.filter, a.view);
+}
+template <int GQ>
+void launch_scores_only_ti(int ti, const AttnArgs& a) {
+    if (ti == 16) launch_scores_only<GQ, 16>(a);
+    else launch_scores_only<GQ, 8>(a);
 }
 
-// P = q.K^T over the candidate range.
 cusa_status run_score(const cusa_params* p, const void* q, const cusa_kv* kv, float* P, int64_t ldp, hipStream_t s,
-                      const int32_t* only_failed, const int32_t* n_failed) {
-    const int g = p->n_q_heads / p->n_kv_heads, H = p->n_q_heads, B = p->batch;
-    const KvView view = make_view(p, kv);
-    const bool paged = kv->layout == CUSA_KV_PAGED;
-    const uint16_t* qf = static_cast<const uint16_t*>(q);
+                      int32_t* only_failed, int32_t* n_failed) {
+    const int g = p->n_q_heads / p->n_kv_heads, BG = p->batch * p->n_kv_heads;
     const int lc_max = kv->max_seq_len - p->window;
-    const int tiles_per_seq = (lc_max + SCORE_ROWS - 1) / SCORE_ROWS;
-    const int64_t n_tiles64 = (int64_t)tiles_per_seq * p->n_kv_heads * B;
-    if (n_tiles64 > 0x7fffffff) return CUSA_ERR_UNSUPPORTED;
-    const int n_tiles = (int)n_tiles64;
-    const int wgs = (n_tiles + SCORE_WAVES - 1) / SCORE_WAVES;
-    const int grid = wgs < SCORE_GRID ? wgs : SCORE_GRID;
+    if (lc_max < 1) return CUSA_OK;
+    const AttnPlan pl = plan_attn(lc_max, BG, g, true);
+    AttnArgs a;
+    a.paged = kv->layout == CUSA_KV_PAGED;
+    a.grid = dim3(pl.n_splits, p->n_kv_heads, p->batch);
+    a.s = s;
+    a.view = make_view(p, kv);
+    a.q = static_cast<const uint16_t*>(q);
+    a.idx = nullptr;
+    a.cnt = nullptr;
+    a.budget = p->budget;
+    a.scale = 0.0f;
+    a.pa = a.pm = nullptr;
+    a.out = nullptr;
+    a.n_splits = pl.n_splits;
+    a.chunk = pl.chunk;
+    a.score.P = P;
+    a.score.ldp = ldp;
+    a.score.window = p->window;
+    a.score.filter.fail = only_failed;                   // nullptr: every group
+    a.score.filter.n_failed = n_failed;
     switch (g) {
-        case 1: launch_score<1>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
-        case 2: launch_score<2>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
-        case 4: launch_score<4>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
-        default: launch_score<8>(paged, grid, s, view, qf, P, ldp, H, p->budget, p->window, tiles_per_seq, n_tiles, only_failed, n_failed); break;
+        case 1: launch_scores_only_ti<1>(pl.ti, a); break;
+        case 2: launch_scores_only_ti<2>(pl.ti, a); break;
+        case 4: launch_scores_only_ti<4>(pl.ti, a); break;
+        default: launch_scores_only_ti<8>(pl.ti, a); break;
     }
     return launch_status();
 }
@@ -657,8 +674,8 @@ cusa_status run_select(const cusa_params* p, const void* q, const cusa_kv* kv, i
                        const FilterState* redo = nullptr) {
     const int H = p->n_q_heads, B = p->batch;
     // redo: the filtered fast path has ranked most heads already; only the flagged ones are scored and ranked here
-    const int32_t* only_failed = redo ? redo->fail : nullptr;
-    const int32_t* n_failed = redo ? redo->n_failed : nullptr;
+    int32_t* only_failed = redo ? redo->fail : nullptr;
+    int32_t* n_failed = redo ? redo->n_failed : nullptr;
     float* P = ws_ptr<float>(ws, w.scores);
     int32_t* rho_head = ws_ptr<int32_t>(ws, w.rho_head);
 

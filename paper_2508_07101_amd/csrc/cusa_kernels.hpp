@@ -1,15 +1,16 @@
 // Device code of libcusa: gfx950 kernels for the CUSA decode hot path.
 //
-//   score_kernel        P = q.K^T over the candidate range (Alg. 1, selection
-//                       layer), one lane per key row, K staged through LDS,
-//                       products accumulated by k = 1 MFMA in column order
 //   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on
 //                       order-preserving keys, then a bitonic sort held in registers
 //                       (lane exchanges by DPP / permlane swaps, LDS across waves)
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
 //                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
 //   attn_kernel         split-K flash-decode over all tokens or over rho
-//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers
+//                       (Eq. 1 / SparseAttention of Alg. 1), GQA group in registers; its
+//                       scoring forms also make P = q.K^T over the candidate range (Alg. 1,
+//                       selection layer): one lane per key row, K staged through LDS,
+//                       products accumulated by k = 1 MFMA in column order
+//   sample_threshold_kernel   per-head thresholds from a sample of the scores (filtered selection)
 //   attn_reduce_kernel  merges the split-K partials and writes bf16
 #pragma once
 #include <hip/hip_runtime.h>
@@ -76,174 +77,18 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// ---------------------------------------------------------------- scoring pass
+// ---------------------------------------------------------------- scoring
 //
-// The unit of work is a tile of 64 consecutive candidate keys of one KV head (16 KB), scored
-// against the GQ query heads of its group by ONE wave; the four waves of a workgroup work
-// independently (own LDS region, own copy of q, no workgroup barrier anywhere), so that while
-// one wave scores, the others' loads keep the memory system busy.  A tile is fetched with
-// coalesced 16-byte loads (16 lanes per 256-byte row, 4 rows per instruction) and parked in
-// LDS, chunk c of row r at slot c ^ (r & 7) so that row reads by consecutive lanes fall into
-// distinct 16-byte bank groups.  Then every lane owns one row.
-//
-// The dot products run on the matrix cores with V_MFMA_F32_4X4X1_16B_F32: one instruction
-// takes, per lane, one binary32 element of q (head = lane % 4) and one of K (the lane's row)
-// and adds the 4 heads x 64 rows of single products to the accumulators.  With k = 1 there
-// is exactly one product (exact: bf16 x bf16 has a 16-bit significand) and one rounded
-// addition per instruction, so walking the 128 columns in order is the left-to-right
-// binary32 sum the selection's bit-exactness rests on -- no reordering inside the
-// instruction can occur.  (Checked bit for bit against a scalar fmaf chain on the device.)
-// q sits in LDS as binary32, one copy per wave, widened once when the wave moves to another
-// group; the 8-float groups of a head are XOR-swizzled by the head number (distinct banks for
-// the four heads a quad of lanes reads, without padding).
-//
-// Wave number v of the grid walks tiles id = v, v + waves, ... (id = (sequence, KV head, tile)
-// in that order) and issues the loads of its next tile before it scores the current one.
-// Rows past the candidate range are clamped to the last candidate (loads stay unconditional
-// and batched); their scores are not stored.
+// The selection scores P = q.K^T are made by the attention kernel's scoring forms (attn_kernel with
+// SCORE; ONLY_SCORES for cusa_select and the second chance).  Their bit-exactness rests on the product
+// chain: V_MFMA_F32_4X4X1_16B_F32 takes, per lane, one binary32 element of q (head = lane % 4) and one
+// of K (the lane's row) and adds the 4 heads x 64 rows of single products to the accumulators.  With
+// k = 1 there is exactly one product (exact: bf16 x bf16 has a 16-bit significand) and one rounded
+// addition per instruction, so walking the 128 columns in order is the left-to-right binary32 sum --
+// no reordering inside the instruction can occur.  (Checked bit for bit against a scalar fmaf chain
+// on the device.)
 
-constexpr int SCORE_ROWS = 64;
-constexpr int SCORE_WAVES = 4;
-
-// Forward declaration: wave-local LDS ordering (defined with the attention kernel).
-__device__ __forceinline__ void wave_lds_sync();
-
-//
-// only_failed (with its counter n_failed): only the groups that have a head whose flag is set are
-// scored, and nothing at all when the counter is zero -- the second chance of the selection's
-// filtered fast path.
-template <int GQ, bool PAGED>
-__global__ __launch_bounds__(64 * SCORE_WAVES) void score_kernel(const uint16_t* __restrict__ q,
-                                                                  float* __restrict__ P, int64_t ldp, int H,
-                                                                  int budget, int window, int tiles_per_seq,
-                                                                  int n_tiles,
-                                                                  const int32_t* __restrict__ only_failed,
-                                                                  const int32_t* __restrict__ n_failed, KvView kv) {
-    if (n_failed && *n_failed == 0) return;
-    constexpr int SETS = (GQ + 3) / 4;                // groups of 4 heads, one accumulator each
-    constexpr int QL = (GQ * D * 2 + 1023) / 1024;    // 16-byte q loads per lane
-    __shared__ u32x4 tile_all[SCORE_WAVES][SCORE_ROWS * 16];
-    // q of the wave's current group as binary32, [head][128], ready for the product chain.  The
-    // 8-float group g of head h sits at group g ^ (h & 3), so that the four heads a quad of lanes
-    // reads at once come from different banks without padding the rows.
-    __shared__ __attribute__((aligned(16))) float q_all[SCORE_WAVES][SETS * 4 * D];
-    const int lane = threadIdx.x & 63, r = lane >> 4, c = lane & 15;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    u32x4* const tile = tile_all[wave];
-    float* const qs = q_all[wave];
-    const int G = kv.G;
-    const int stride = gridDim.x * SCORE_WAVES;
-    for (int i = lane; i < SETS * 4 * D; i += 64) qs[i] = 0.0f;   // heads beyond GQ contribute zeros
-
-    // next tile at or after `id` (stride: all waves of the grid) that has candidates; n_tiles if none
-    auto next_valid = [&](int id, int& b, int& kvh, int& t0, int& Lc) __attribute__((always_inline)) {
-        for (; id < n_tiles; id += stride) {
-            const int seq_head = id / tiles_per_seq;
-            b = seq_head / G;
-            kvh = seq_head - b * G;
-            t0 = (id - seq_head * tiles_per_seq) * SCORE_ROWS;
-            const int L = kv.seq_lens[b];
-            Lc = L - window;
-            if (L > budget && t0 < Lc) {              // L <= budget: rho = everything, nothing to score
-                if (!only_failed) return id;
-                int any = 0;
-                for (int hh = 0; hh < GQ; ++hh) any |= only_failed[b * H + kvh * GQ + hh];
-                if (any) return id;
-            }
-        }
-        return n_tiles;
-    };
-    int b = 0, kvh = 0, t0 = 0, Lc = 0;               // tile being scored (none yet)
-    int qb = -1, qkvh = -1;                           // the group whose q is in LDS
-    bool have_cur = false;
-    int nb, nkvh, nt0, nLc;
-    int nid = next_valid(blockIdx.x * SCORE_WAVES + wave, nb, nkvh, nt0, nLc);
-    while (true) {
-        const bool have_next = nid < n_tiles;
-        const bool new_q = have_next && (nb != qb || nkvh != qkvh);
-        u32x4 stage[16];
-        u32x4 qstage[QL];
-        if (have_next) {                              // loads of the next tile, in flight during the scoring below
-            int64_t off[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int t = min(nt0 + i * 4 + r, nLc - 1);
-                off[i] = row_offset<PAGED>(kv, nb, nkvh, t) + c * 8;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) stage[i] = stream_load(kv.k + off[i]);
-            if (new_q) {
-                const uint16_t* __restrict__ qg = q + ((int64_t)nb * H + (int64_t)nkvh * GQ) * D;
-#pragma unroll
-                for (int j = 0; j < QL; ++j)
-                    qstage[j] = *reinterpret_cast<const u32x4*>(qg + min((j * 64 + lane) * 8, GQ * D - 8));
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (have_cur) {
-            f32x4 acc[SETS];
-#pragma unroll
-            for (int s = 0; s < SETS; ++s) acc[s] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int cc = 0; cc < 16; ++cc) {
-                const u32x4 w = tile[lane * 16 + (cc ^ (lane & 7))];
-                float kf[8];
-                unpack8(make_uint4(w.x, w.y, w.z, w.w), kf);
-                float qf[SETS][8];
-#pragma unroll
-                for (int s = 0; s < SETS; ++s) {
-                    const float* const src = &qs[(s * 4 + (lane & 3)) * D + ((cc ^ (lane & 3)) << 3)];
-                    const f32x4 qa = *reinterpret_cast<const f32x4*>(src), qb = *reinterpret_cast<const f32x4*>(src + 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        qf[s][e] = qa[e];
-                        qf[s][4 + e] = qb[e];
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int s = 0; s < SETS; ++s)
-                        acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(qf[s][e], kf[e], acc[s], 0, 0, 0);
-            }
-            const int t = t0 + lane;
-            if (t < Lc) {
-#pragma unroll
-                for (int s = 0; s < SETS; ++s)
-#pragma unroll
-                    for (int h = 0; h < 4; ++h)
-                        if (s * 4 + h < GQ) P[((int64_t)b * H + kvh * GQ + s * 4 + h) * ldp + t] = acc[s][h];
-            }
-        }
-        if (!have_next) break;
-        wave_lds_sync();                              // this wave is done reading its tile and q
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = i * 4 + r;
-            tile[row * 16 + (c ^ (row & 7))] = stage[i];
-        }
-        if (new_q) {
-#pragma unroll
-            for (int j = 0; j < QL; ++j) {
-                const int e0 = (j * 64 + lane) * 8;   // first of the lane's 8 consecutive elements of the group's q
-                if (e0 < GQ * D) {
-                    const int hd = e0 >> 7, grp = (e0 & (D - 1)) >> 3;
-                    float wide[8];
-                    unpack8(make_uint4(qstage[j].x, qstage[j].y, qstage[j].z, qstage[j].w), wide);
-                    float* const dst = &qs[hd * D + ((grp ^ (hd & 3)) << 3)];
-                    *reinterpret_cast<f32x4*>(dst) = f32x4{wide[0], wide[1], wide[2], wide[3]};
-                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{wide[4], wide[5], wide[6], wide[7]};
-                }
-            }
-            qb = nb;
-            qkvh = nkvh;
-        }
-        wave_lds_sync();
-        b = nb; kvh = nkvh; t0 = nt0; Lc = nLc;
-        have_cur = true;
-        nid = next_valid(nid + stride, nb, nkvh, nt0, nLc);
-    }
-}
+constexpr int SCORE_ROWS = 64;                        // tokens of a sample tile
 
 // ---------------------------------------------------------------- block helpers
 
@@ -1047,7 +892,7 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 // compacted per head) and the top-k ranks among them.  theta is only a guess, so everything that
 // depends on it is checked: a head whose kept candidates turn out fewer than k (theta too high) or more
 // than the buffers hold (theta too low, or many equal scores) is flagged, and the flagged heads are
-// scored and ranked again the ordinary way (score_kernel and topk_kernel in their only_failed forms).
+// scored and ranked again the ordinary way (the scores-only pass and topk_kernel in their flagged-only forms).
 // The result never depends on theta; only the time does.
 //
 // The sample of a head has n_s candidates out of n (every position in a sampled tile that is a
@@ -1464,10 +1309,10 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // SCORE (selection layer, all tokens): the scores of the candidate range [0, L - window) are also
-// written to P[b][head][t] (row stride ldp), bit for bit what score_kernel writes, so the layer's K
-// is read once for both (Alg. 1 computes the layer's output and P from the same K).  q.k then runs
-// as the k = 1 MFMA chain of score_kernel -- the pinned left-to-right binary32 sum -- instead of
-// the k = 4 bf16 MFMA, and the softmax uses those same values.
+// written to P[b][head][t] (row stride ldp), so the layer's K is read once for both (Alg. 1 computes
+// the layer's output and P from the same K).  q.k then runs as the k = 1 MFMA chain -- the pinned
+// left-to-right binary32 sum (see "scoring" above) -- instead of the k = 4 bf16 MFMA, and the softmax
+// uses those same values.
 //
 // lse (optional): log2 of each head's softmax denominator, M + log2(l) with scores scaled by
 // sm_scale * log2(e); written by whoever writes the head's output (this kernel or the reduce).
@@ -1476,7 +1321,12 @@ __device__ __forceinline__ void wave_lds_sync() {
 // -- the head-to-head selection the paper compares with (Sec. 3.2, the generalization figure) --
 // so a workgroup serves one query head, blockIdx.y counts query heads (G of them) and head y reads
 // KV head y >> hshift.  Nothing is shared inside a GQA group: each head fetches its own rows.
-template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_HEAD = false, bool FILTER = false>
+//
+// ONLY_SCORES (a form of SCORE): the scores and nothing else -- no V rows, no softmax, no output.  This
+// is cusa_select's scoring pass and the second chance of the filtered selection: with flt.fail set, only
+// the groups that have a flagged head are scored, and nothing at all when the counter *flt.n_failed is 0.
+template <int GQ, int TI, bool SPARSE, bool PAGED, bool SCORE = false, bool PER_HEAD = false, bool FILTER = false,
+          bool ONLY_SCORES = false>
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, const int32_t* __restrict__ seq_lens,
     const uint16_t* __restrict__ q, int budget, int n_splits, int chunk, int G, float scale_log2e,
@@ -1484,6 +1334,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     float* __restrict__ P, int64_t ldp, int window, int hshift, FilterState flt, KvView kv) {
     static_assert(!(SCORE && SPARSE), "scores are emitted by the pass over all tokens");
     static_assert(!FILTER || SCORE, "the filter is a form of the scoring variant");
+    static_assert(!ONLY_SCORES || (SCORE && !FILTER), "scores only: the dense scoring variant without the attention");
     static_assert(!PER_HEAD || (SPARSE && GQ == 1), "per-head token lists: one query head per workgroup");
     constexpr int TILE = TI * 4;                      // tokens per wave iteration (<= 64)
     constexpr int WG_TILE = TILE * ATTN_WAVES;
@@ -1568,7 +1419,17 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     }
     bool q_parked = false;
     const int L = seq_lens[b];
-    const int n = SPARSE ? min(cnt[b], budget) : L;
+    if constexpr (ONLY_SCORES) {
+        if (L <= budget) return;                         // rho is every token: nothing is scored
+        if (flt.fail) {                                  // the second chance: flagged heads' groups only
+            if (*flt.n_failed == 0) return;
+            int any = 0;
+#pragma unroll
+            for (int h = 0; h < GQ; ++h) any |= flt.fail[head0 + h];
+            if (!any) return;
+        }
+    }
+    const int n = SPARSE ? min(cnt[b], budget) : ONLY_SCORES ? L - window : L;   // scores only: the candidate range
     // Everything the first tile's addresses depend on is requested above and has to be here
     // before the first branch; otherwise the compiler sinks each load behind the branch that
     // precedes its first use and the kernel starts with a chain of dependent memory round trips.
@@ -1607,7 +1468,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     constexpr bool PREFETCH = !SCORE;
     // The scoring variant of a group of 8 has no registers for K and V rows at once (64 each at 64-token
     // tiles, beside 64 accumulators): its V rows are requested once the K rows are parked in LDS.
-    constexpr bool V_LATE = SCORE && (GQ >= 8 || (FILTER && GQ >= 4));
+    constexpr bool V_LATE = !ONLY_SCORES && SCORE && (GQ >= 8 || (FILTER && GQ >= 4));
     u32x4 kreg[TI], vreg[TI];
     int64_t off[TI];
     // a valid position for row load i of the tile that starts at list entry t_ (an index outside the
@@ -1759,7 +1620,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             // order, so the scores are under way while the V rows are still arriving.
             request_k();
         }
-        if constexpr (!V_LATE) {
+        if constexpr (!V_LATE && !ONLY_SCORES) {
 #pragma unroll
             for (int i = 0; i < TI; ++i) vreg[i] = row_load<PER_HEAD>(kv.v + off[i]);
         }
@@ -1885,6 +1746,10 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
                 }
             }
         }
+        if constexpr (ONLY_SCORES) {
+            wave_lds_sync();                              // the tile buffer is rewritten next iteration
+            continue;
+        }
         const bool valid = t0 + tl < end;
         float corr[GQ];
 #pragma unroll
@@ -1947,6 +1812,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
             flush_scores(begin + it_staged * WG_TILE, (it - it_staged) * WG_TILE);
         }
     }
+    if constexpr (ONLY_SCORES) return;
     // Merge.  Inside the wave the four row groups are folded with lane swaps: of the N = 8 GQ
     // values of a lane, two folds leave N / 4 complete sums, those with flat index (head * 8 +
     // column) v0 .. v0 + N/4 - 1 where v0 depends on the row group.  The wave parks them in its
