@@ -1383,6 +1383,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     // Workgroups go to the 8 XCDs round-robin in launch order (blockIdx.x fastest).  With ragged
     // lengths the low splits are the busy ones; starting each (sequence, KV head) at a different
     // block spreads them evenly over the XCDs instead of loading the first ones.
+    if constexpr (ONLY_SCORES) {                         // the second chance with nothing flagged: out before any other load is asked for
+        if (flt.fail && *flt.n_failed == 0) return;
+    }
     const int gy = blockIdx.y, b = blockIdx.z, H = G * GQ;
     const int kvh = PER_HEAD ? gy >> hshift : gy;
     const int split = (int)((blockIdx.x + gy + G * b) % (unsigned)n_splits);
@@ -1422,7 +1425,6 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_kernel(
     if constexpr (ONLY_SCORES) {
         if (L <= budget) return;                         // rho is every token: nothing is scored
         if (flt.fail) {                                  // the second chance: flagged heads' groups only
-            if (*flt.n_failed == 0) return;
             int any = 0;
 #pragma unroll
             for (int h = 0; h < GQ; ++h) any |= flt.fail[head0 + h];
