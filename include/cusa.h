@@ -204,7 +204,10 @@ cusa_status cusa_full_attn(const cusa_params* params, const void* q, const cusa_
 
 /* A selection layer in one call (the selection branch of Alg. 1): out = FullAttention(q, C[:])
  * and rho = the selection of cusa_select, from one pass over K (the pass that computes the
- * output also writes the scores).  idx and cnt as in cusa_select (bit for bit the same rho);
+ * output also writes the scores -- or, for a layer with many scores, only those above a
+ * per-head threshold guessed from a sample; heads whose guess fails are scored and ranked again,
+ * so the result does not depend on it: cusa_ws_layout.filtered_select).  idx and cnt as in
+ * cusa_select (bit for bit the same rho);
  * out as in cusa_full_attn up to binary32 rounding order.  This is what cusa_decode_step runs
  * for a SELECT layer; a caller that drives the layers itself uses it instead of
  * cusa_full_attn followed by cusa_select, which read K twice. */
