@@ -121,6 +121,9 @@ typedef struct {
                                        cusa_decode_step) keeps only the scores that can reach a head's top-k
                                        and writes no score array; `scores` is then defined after cusa_select
                                        only.  rho_head, idx and cnt are the same either way. */
+    size_t  second_chance_offset;   /* filtered_select = 1: an int32 there holds, after such a layer, how many
+                                       heads' thresholds failed and were scored and ranked again (a
+                                       diagnostic: the result does not depend on it) */
 } cusa_ws_layout;
 
 /* Bytes of device workspace any of the calls below needs for `params` and

@@ -47,7 +47,7 @@ class CusaKv(ctypes.Structure):
 class CusaWsLayout(ctypes.Structure):
     _fields_ = [("scores_offset", ctypes.c_size_t), ("ld_scores", ctypes.c_int64),
                 ("rho_head_offset", ctypes.c_size_t), ("k", ctypes.c_int32), ("total_bytes", ctypes.c_size_t),
-                ("filtered_select", ctypes.c_int32)]
+                ("filtered_select", ctypes.c_int32), ("second_chance_offset", ctypes.c_size_t)]
 
 
 class CusaError(RuntimeError):

@@ -731,10 +731,10 @@ void launch_sample_threshold_g(const cusa_params* p, const void* q, const cusa_k
     const uint16_t* qf = static_cast<const uint16_t*>(q);
     if (kv->layout == CUSA_KV_PAGED)
         launch(KID_SAMPLE_THRESHOLD, sample_threshold_kernel<GQ, true>, grid, SEL_THREADS, shmem, s, qf, p->n_q_heads, k, p->budget,
-               p->window, sp.tile_step, sp.n_slots, f, view);
+               p->window, sp.n_slots, f, view);
     else
         launch(KID_SAMPLE_THRESHOLD, sample_threshold_kernel<GQ, false>, grid, SEL_THREADS, shmem, s, qf, p->n_q_heads, k, p->budget,
-               p->window, sp.tile_step, sp.n_slots, f, view);
+               p->window, sp.n_slots, f, view);
 }
 void launch_sample_threshold(const cusa_params* p, const void* q, const cusa_kv* kv, const SamplePlan& sp,
                              const FilterState& f, int k, hipStream_t s) {
@@ -813,6 +813,7 @@ cusa_status cusa_workspace_layout(const cusa_params* params, int32_t max_seq_len
     layout->k = w.k;
     layout->total_bytes = w.total;
     layout->filtered_select = filtered_select(params, max_seq_len) ? 1 : 0;
+    layout->second_chance_offset = w.f_nfailed;
     return CUSA_OK;
 }
 

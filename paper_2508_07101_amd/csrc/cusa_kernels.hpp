@@ -886,8 +886,8 @@ __global__ __launch_bounds__(SEL_THREADS) void union_kernel(const int32_t* __res
 // Writing a score for every (head, cached token) is what the selection layer's pass pays most for
 // beyond its reads, and the per-head top-k then walks all of them again.  The fast path of a selection
 // layer writes only the scores that can matter.  A first, small launch (this kernel) scores a SAMPLE
-// of the tokens -- every tile_step-th tile of 64 -- and takes, per head, a threshold theta from the
-// sample such that with overwhelming probability at least k and not many more than k of the head's
+// of the tokens -- every 16th tile of 64, fewer of a very long sequence -- and takes, per head, a
+// threshold theta from the sample such that with overwhelming probability at least k and not many more than k of the head's
 // candidates score >= theta; the pass then keeps only those (as (score key, position) composites,
 // compacted per head) and the top-k ranks among them.  theta is only a guess, so everything that
 // depends on it is checked: a head whose kept candidates turn out fewer than k (theta too high) or more
@@ -933,7 +933,7 @@ __host__ __device__ inline int filter_sample_rank(float k_eff, float n, float n_
 
 template <int GQ, bool PAGED>
 __global__ __launch_bounds__(SEL_THREADS) void sample_threshold_kernel(const uint16_t* __restrict__ q, int H, int k,
-                                                                        int budget, int window, int tile_step,
+                                                                        int budget, int window,
                                                                         int n_slots_max, FilterState f, KvView kv) {
     static_assert(GQ <= 4, "a quarter of the workgroup per head");
     extern __shared__ uint32_t thr_lds_buf[];         // keys [GQ][n_slots_max], then bins [GQ][THR_BINS]
@@ -955,8 +955,11 @@ __global__ __launch_bounds__(SEL_THREADS) void sample_threshold_kernel(const uin
     }
     const int Lc = L - window, n = Lc - f.n_sink, k_eff = k < n ? k : n;
     const int tiles_all = (Lc + 63) >> 6;
-    // sampled tiles: <= n_slots_max / 64 for every sequence within the bound the launch was planned for
-    const int n_tiles = min((tiles_all + tile_step - 1) / tile_step, n_slots_max >> 6);
+    // every SAMPLE_STEP-th tile of this sequence, or as many tiles as the launch has LDS for (a short
+    // sequence in a cache laid out for long ones is still sampled densely)
+    const int max_tiles = n_slots_max >> 6;
+    const int tile_step = max(SAMPLE_STEP, (tiles_all + max_tiles - 1) / max_tiles);
+    const int n_tiles = (tiles_all + tile_step - 1) / tile_step;
     const int n_slots = n_tiles * 64;
 
     // The sample's scores come from V_MFMA_F32_16X16X16_BF16, 16 tokens x 16 heads (GQ of them real) per

@@ -17,23 +17,27 @@ def params_of(inp: Inputs, rank_mode: int = cb.RANK_FIRST_OCCURRENCE) -> cb.Cusa
                           head_dim=w.head_dim, rank_mode=rank_mode, n_sink=w.n_sink)
 
 
-def kv_of(inp: Inputs, layer_pos: int) -> cb.KvCache:
+def kv_of(inp: Inputs, layer_pos: int, max_len: Optional[int] = None) -> cb.KvCache:
     lay = inp.layers[layer_pos]
-    return cb.KvCache(lay.k, lay.v, inp.seq_lens, max(inp.seq_lens_host) + inp.workload.grow_room, inp.block_table)
+    bound = max(inp.seq_lens_host) + inp.workload.grow_room if max_len is None else max_len
+    return cb.KvCache(lay.k, lay.v, inp.seq_lens, bound, inp.block_table)
 
 
 class StepRunner:
     """One decode step (attention part of Alg. 1) over ``inp.layers`` with ``schedule``."""
 
-    def __init__(self, inp: Inputs, schedule: Optional[List[int]] = None, rank_mode: int = cb.RANK_FIRST_OCCURRENCE):
+    def __init__(self, inp: Inputs, schedule: Optional[List[int]] = None, rank_mode: int = cb.RANK_FIRST_OCCURRENCE,
+                 max_len: Optional[int] = None):
         w = inp.workload
         self.inp = inp
         self.schedule = list(w.schedule if schedule is None else schedule)
         assert len(self.schedule) == len(inp.layers)
         dev = inp.seq_lens.device
         self.params = params_of(inp, rank_mode)
-        self.max_len = max(inp.seq_lens_host) + w.grow_room   # capacity: the lengths may grow up to it
-        self.kvs = [kv_of(inp, i) for i in range(len(inp.layers))]
+        # capacity: the lengths may grow up to it (max_len: a bound above what the caches hold, which no kernel reads up to)
+        self.max_len = max(inp.seq_lens_host) + w.grow_room if max_len is None else max_len
+        assert self.max_len >= max(inp.seq_lens_host)
+        self.kvs = [kv_of(inp, i, self.max_len) for i in range(len(inp.layers))]
         self.outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
                      for _ in inp.layers]
         self.idx = torch.full((w.batch, w.budget), -1, dtype=torch.int32, device=dev)
@@ -90,6 +94,12 @@ class StepRunner:
 
     def full(self, layer_pos: int):
         cb.full_attn(self.params, self.inp.layers[layer_pos].q, self.kvs[layer_pos], self.outs[layer_pos], self.ws)
+
+    def second_chance_heads(self) -> int:
+        """Heads of the last filtered selection layer whose threshold failed (they were scored and ranked again)."""
+        lay = cb.workspace_layout(self.params, self.max_len)
+        assert lay.filtered_select
+        return int(self.ws[lay.second_chance_offset: lay.second_chance_offset + 4].view(torch.int32).item())
 
     def filtered_select(self) -> bool:
         """Whether a selection layer of this size keeps candidates instead of writing the score array."""

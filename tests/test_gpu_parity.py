@@ -546,6 +546,7 @@ def test_filtered_selection_layer_fast_path_and_its_second_chance():
     assert r.filtered_select()
     calls = _kernel_calls(r.run)
     assert calls["sample_threshold_kernel"] == 1 and calls["topk_kernel<filtered>"] == 1
+    assert r.second_chance_heads() == 0                  # random scores: every guess holds
     check_select(inp, r, 0, check_scores=False)
     for i, kind in enumerate(w.schedule):
         check_attention(inp, r, i, kind, seqs=[0, 7])
@@ -570,6 +571,7 @@ def test_filtered_selection_layer_fast_path_and_its_second_chance():
         rows = k[b, :, :Lb][:, chosen].float() * 0.05 + boost[:, None, :]
         k[b, :, torch.nonzero(chosen).squeeze(1)] = rows.to(torch.bfloat16)
     r.run()
+    assert r.second_chance_heads() >= w.n_q_heads        # the two sequences' heads were found out
     check_select(inp, r, 0, check_scores=False)
     check_attention(inp, r, 1, LAYER_SPARSE, seqs=[3, 5])
 
@@ -592,6 +594,20 @@ def test_filtered_selection_layer_group_sizes_layouts_sinks(H, paged, sinks, k):
     check_select(inp, r, 0, seqs=range(0, B, 3), check_scores=False)
     check_attention(inp, r, 0, LAYER_SELECT, seqs=[1, 2])
     check_attention(inp, r, 1, LAYER_SPARSE, seqs=[0, 2])
+
+
+def test_filtered_selection_with_a_capacity_far_above_the_lengths():
+    """The bound max_seq_len is a capacity (here 8 times the longest sequence): the sample of a sequence is
+    taken at the density its own length allows, so the thresholds hold and no head needs the second chance."""
+    lens = tuple(int(x) for x in np.random.default_rng(5).integers(9000, 12000, size=16))
+    w = small("filter_cap", batch=16, seq_len=12000, lengths=lens, budget=1024, window=256, n_planted=5)
+    inp = wl.make_inputs(w, DEV)
+    r = StepRunner(inp, max_len=96000)
+    assert r.filtered_select()
+    r.run()
+    check_select(inp, r, 0, seqs=range(0, 16, 3), check_scores=False)
+    n_failed = r.second_chance_heads()
+    assert n_failed == 0, f"{n_failed} heads took the second chance"
 
 
 def test_many_rows_take_the_lean_streamed_topk():
