@@ -431,6 +431,12 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
         "rooflines": rooflines,
         "kernels": kernels,
     }
+    if args.entry == "step" and 1 in sched and r.filtered_select():
+        # the selection layer kept only the candidates above sampled thresholds; heads whose threshold failed
+        # were scored and ranked again the ordinary way (the result is the same either way)
+        run_step()
+        torch.cuda.synchronize()
+        rec["filtered_selection"] = {"second_chance_heads": r.second_chance_heads(), "heads": w.batch * w.n_q_heads}
     if full_s is not None and args.entry == "step":
         rec["full_attention_all_layers_us"] = round(full_s * 1e6, 2)
         rec["speedup_vs_full_attention"] = round(full_s / step_s, 3)
