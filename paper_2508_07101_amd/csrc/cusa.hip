@@ -214,16 +214,19 @@ int plan_topk_slices(int64_t rows, int lc_max, int k) {
     return s < 1 ? 1 : (int)s;
 }
 
-// Sampling plan of the filtered fast path for sequences of up to lc candidate positions: every
-// tile_step-th tile of 64 tokens, n_slots sample slots per head.
+// Sampling plan of the filtered fast path for sequences of up to lc candidate positions: the kernel
+// samples every SAMPLE_STEP-th tile of 64 tokens of a sequence, or as many tiles as it has LDS for
+// (n_slots sample slots per head); tile_step is the step of a sequence as long as the bound.
 struct SamplePlan {
     int tile_step, n_slots;
 };
 SamplePlan plan_sample(int64_t lc) {
     const int64_t tiles_all = (lc + SCORE_ROWS - 1) / SCORE_ROWS;
-    int64_t step = (tiles_all + SAMPLE_MAX_TILES - 1) / SAMPLE_MAX_TILES;
+    int64_t tiles = (tiles_all + SAMPLE_STEP - 1) / SAMPLE_STEP;
+    if (tiles > SAMPLE_MAX_TILES) tiles = SAMPLE_MAX_TILES;
+    int64_t step = (tiles_all + tiles - 1) / tiles;
     if (step < SAMPLE_STEP) step = SAMPLE_STEP;
-    return {(int)step, (int)((tiles_all + step - 1) / step) * SCORE_ROWS};
+    return {(int)step, (int)tiles * SCORE_ROWS};
 }
 int filter_cap_for(int k) { return k <= 2048 ? 4096 : 8192; }
 size_t sample_lds_bytes(int g, int n_slots) { return (size_t)g * ((size_t)n_slots + THR_BINS) * 4; }
