@@ -103,6 +103,26 @@ def step_durations(fn, steps, torch):
     return [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(steps)]
 
 
+def cold_step_durations(fn, steps, torch, cb):
+    """Durations of `steps` calls (microseconds), each after a streaming read of 1 GiB that turns the caches
+    over (the 256 MB last-level cache included); the read is outside the timed interval."""
+    junk = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    junk.fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        cb.probe_stream_read(junk, sink)
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    out = [a.elapsed_time(b) * 1e3 for a, b in ev]
+    del junk
+    torch.cuda.empty_cache()
+    return out
+
+
 def kernel_bytes(w, lens, acc):
     """Algorithmic bytes of ONE launch of each bandwidth-bound kernel (all sequences of the batch)."""
     G, K, W = w.n_kv_heads, w.budget, w.window
@@ -414,6 +434,15 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
                                   "us_per_step": k["us_per_step"]})
 
     sb = acc.step_bytes(sched, lens, w.n_kv_heads, w.budget, w.window)
+    # A step over less than a few last-level caches' worth of KV finds part of it cached from the step before
+    # (c1, c4: one layer, repeated): those figures are warm.  The cold figure beside them has the caches turned
+    # over before every step.
+    kv_bytes = int(sum(2 * w.n_kv_heads * L * w.head_dim * 2 for L in lens) * (1 if w.same_layer_sparse else w.n_layers))
+    cold = None
+    if kv_bytes < (1 << 30) and w.grow_room == 0 and not args.graph:
+        cd = cold_step_durations(run_step, steps, torch, cb)
+        cold = {"median": round(statistics.median(cd), 2), "min": round(min(cd), 2), "steps": steps,
+                "how": "1 GiB streaming read before every step, outside the timed interval"}
     rec = {
         "us_per_step": {"mean": round(step_s * 1e6, 2), "median": round(statistics.median(durs), 2),
                         "min": round(min(durs), 2), "steps": steps, "warmup": warmup},
@@ -426,6 +455,8 @@ def measure(name, args, torch, acc, cb, wl, StepRunner):
                    "kv_cache_bytes": int(sum(2 * w.n_kv_heads * L * w.head_dim * 2 for L in lens) *
                                          (1 if w.same_layer_sparse else w.n_layers)),
                    **({"head_overlap": args.head_overlap} if args.head_overlap is not None else {})},
+        "cache": "warm (the step's KV fits the last-level cache in part; see cold_us_per_step)" if cold else "cold",
+        **({"cold_us_per_step": cold} if cold else {}),
         "step_algorithmic_bytes": sb["total"],
         "step_achieved_GBs": round(sb["total"] / step_s / 1e9, 1),
         "rooflines": rooflines,
