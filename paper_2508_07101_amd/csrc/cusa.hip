@@ -487,7 +487,7 @@ constexpr size_t SEL_LDS_MAX = (size_t)UNION_MAX_POSITIONS / 8;   // the selecti
 
 template <int ITEMS, int MTOP>
 constexpr size_t topk_lds_bytes() {
-    return ((size_t)MTOP * SEL_THREADS + topk_list_cap(ITEMS, MTOP)) * sizeof(uint64_t);
+    return ((size_t)MTOP * SEL_THREADS + topk_area_entries(ITEMS, MTOP)) * sizeof(uint64_t);
 }
 
 bool grant_lds(const void* fn, size_t bytes) {

@@ -274,6 +274,11 @@ __device__ __forceinline__ int wave_reserve(int mine, int* counter) {
 __host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
     return (items > 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
 }
+// 8-byte entries of LDS behind the sort buffer: the candidate list, later the quick ranking's segments
+// (mtop * 1024 composites) and its 2048 bin counters.
+__host__ __device__ constexpr int topk_area_entries(int items, int mtop) {
+    return topk_list_cap(items, mtop) > mtop * 1024 + 1024 ? topk_list_cap(items, mtop) : mtop * 1024 + 1024;
+}
 
 // Value of lane (l ^ STRIDE) for STRIDE < 64 without the LDS crossbar: DPP moves inside a 16-lane
 // row, row/half swaps beyond.
@@ -321,7 +326,7 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
 // with zeros, in parts[row][slice][k]; the k best of a row are among the k best of its slices, so a
 // second launch (MERGE) selects and ranks among those n_slices * k composites instead of the row.
 template <int ITEMS, int MTOP, bool MERGE = false>
-__global__ __launch_bounds__(SEL_THREADS, (ITEMS == -1 || (MERGE && ITEMS <= 4)) ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
+__global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)) && MTOP <= 4) ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
                                                             int budget, int window, int raw_keys, int n_sink,
@@ -506,10 +511,12 @@ __global__ __launch_bounds__(SEL_THREADS, (ITEMS == -1 || (MERGE && ITEMS <= 4))
     // 1-3 for candidates delivered by scan_fn: the remaining digits of the k_eff-th best score key
     // T (its top digit is already in st), the position bound among the keys equal to T when they
     // straddle the cut (rare), and the survivors' composites compacted into sort_buf in any order.
+    uint32_t sel_T = 0u;                               // the k_eff-th best score key, once finish has run
     auto finish = [&](auto scan_fn) {
         radix_select(1, k_eff, 0u, scan_fn, [](uint32_t skey, int, uint32_t* key) { *key = skey; return true; },
                      hist, scratch, &st);
         const uint32_t T = st.prefix;
+        sel_T = T;
         const int need_eq = st.need, count_eq = st.count_eq;
         __syncthreads();
         uint32_t pos_bound = 0xffffffffu;              // take every tie
@@ -614,9 +621,96 @@ __global__ __launch_bounds__(SEL_THREADS, (ITEMS == -1 || (MERGE && ITEMS <= 4))
         for (int i = threadIdx.x; i < k; i += SEL_THREADS) my_parts[i] = i < k_eff ? sort_buf[i] : 0;
         return;
     }
+    // 3a. The ranking, the quick way: 2048 bins divide the survivors' score range evenly by value
+    //     (monotone in the key, so bins are in rank order), a counting sort puts every survivor into its
+    //     bin's segment, and inside a segment -- a few entries, unless scores repeat -- a survivor's rank
+    //     is the number of entries that beat it.  Every survivor then writes its pick at its rank.  The
+    //     range is [score of T, that + 6 x the survivors' mean excess over it], not up to the best score:
+    //     a few very large scores (attention sinks, hot tokens) would otherwise stretch the bins over
+    //     empty space and crowd the rest; whatever lies above shares the first bin, which may hold more.
+    //     About a fifth of the instructions of the network below, which remains for rows with crowded
+    //     bins (many equal scores), non-finite scores and raw keys.
+    if (!raw_keys) {
+        constexpr int RBINS = 2048, RMAX = 32, RMAX_FIRST = 512;   // bins; entries a bin / the first bin may hold
+        uint64_t* const seg = cand;                      // NSORT composites, ordered by bin
+        int* const rbin = reinterpret_cast<int*>(cand + NSORT);   // per bin: count, then first index
+        __shared__ float rk_excess;
+        __shared__ int rk_crowd, rk_first;
+        const int tid = threadIdx.x;
+        if (tid == 0) {
+            rk_excess = 0.0f;
+            rk_crowd = 0;
+        }
+        for (int i = tid; i < RBINS; i += SEL_THREADS) rbin[i] = 0;
+        uint64_t mine[MTOP];
+        const float s_lo = key_score(sel_T);
+        float excess = 0.0f;
+#pragma unroll
+        for (int j = 0; j < MTOP; ++j) {
+            const int i = tid + j * SEL_THREADS;
+            mine[j] = i < k_eff ? sort_buf[i] : 0;
+            if (i < k_eff) excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) excess += __shfl_xor(excess, o);
+        __syncthreads();                                 // rk_excess, rbin are cleared
+        if (lane_id() == 0) atomicAdd(&rk_excess, excess);
+        __syncthreads();
+        const float range = 6.0f * rk_excess / (float)k_eff;
+        bool quick = range > 0.0f && range < 3.0e38f;    // workgroup-uniform (not so: all scores equal, or not finite)
+        const float scale = quick ? (float)(RBINS - 1) / range : 0.0f;
+        auto bin_of = [&](uint64_t cv) {                 // bin 0 holds the best scores
+            const int up = (int)((key_score((uint32_t)(cv >> 32)) - s_lo) * scale);
+            return RBINS - 1 - (up < 0 ? 0 : up > RBINS - 1 ? RBINS - 1 : up);
+        };
+        int slot[MTOP];
+        if (quick) {
+#pragma unroll
+            for (int j = 0; j < MTOP; ++j)
+                if (tid + j * SEL_THREADS < k_eff) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
+        }
+        __syncthreads();
+        {   // counts -> first indices (thread i owns bins 2i, 2i + 1); the most crowded bin
+            const int c0 = rbin[2 * tid], c1 = rbin[2 * tid + 1];
+            int total;
+            const int first = block_scan_excl(c0 + c1, scratch, &total);
+            int crowd = tid == 0 ? c1 : (c0 > c1 ? c0 : c1);   // bin 0 is looked at on its own
+            if (tid == 0) rk_first = c0;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const int other = __shfl_xor(crowd, o);
+                crowd = other > crowd ? other : crowd;
+            }
+            if (lane_id() == 0) atomicMax(&rk_crowd, crowd);
+            rbin[2 * tid] = first;
+            rbin[2 * tid + 1] = first + c0;
+        }
+        __syncthreads();
+        quick = quick && rk_crowd <= RMAX && rk_first <= RMAX_FIRST;
+        if (quick) {
+#pragma unroll
+            for (int j = 0; j < MTOP; ++j)
+                if (tid + j * SEL_THREADS < k_eff) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
+            __syncthreads();
+            int32_t* __restrict__ out = rho_head + (int64_t)b * k * H + h;
+#pragma unroll
+            for (int j = 0; j < MTOP; ++j) {
+                const int i = tid + j * SEL_THREADS;
+                if (i < k_eff) {
+                    const uint64_t cv = seg[i];
+                    const int bn = bin_of(cv), lo = rbin[bn], hi = bn == RBINS - 1 ? k_eff : rbin[bn + 1];
+                    int rank = lo;
+                    for (int q = lo; q < hi; ++q) rank += seg[q] > cv ? 1 : 0;
+                    out[(int64_t)rank * H] = (int32_t)~(uint32_t)cv;
+                }
+            }
+            return;
+        }
+        __syncthreads();                                 // the bins' area is the list's again below (not used any more)
+    }
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
-    // Bitonic network over NSORT = MTOP * 1024 composites, MTOP per thread in registers:
+    // 3b. Bitonic network over NSORT = MTOP * 1024 composites, MTOP per thread in registers:
     // element j of thread (wave, lane) is index wave*64*MTOP + j*64 + lane.  A step with
     // stride < 64 exchanges between lanes of a wave, a stride of 64 .. 32*MTOP between the
     // thread's own registers, and only larger strides go through LDS with workgroup barriers.
