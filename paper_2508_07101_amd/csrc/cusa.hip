@@ -485,9 +485,9 @@ cusa_status run_attention_per_head(const cusa_params* p, const void* q, const cu
 // calls only enqueue kernels.
 constexpr size_t SEL_LDS_MAX = (size_t)UNION_MAX_POSITIONS / 8;   // the selection bitmaps
 
-template <int ITEMS, int MTOP>
+template <int ITEMS, int MTOP, bool MERGE = false>
 constexpr size_t topk_lds_bytes() {
-    return ((size_t)MTOP * SEL_THREADS + topk_area_entries(ITEMS, MTOP)) * sizeof(uint64_t);
+    return ((size_t)MTOP * SEL_THREADS + topk_area_entries(ITEMS, MTOP, MERGE)) * sizeof(uint64_t);
 }
 
 bool grant_lds(const void* fn, size_t bytes) {
@@ -501,10 +501,10 @@ bool grant_lds(const void* fn, size_t bytes) {
 
 template <int ITEMS, bool MERGE = false>
 bool grant_topk_items() {
-    return grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 1, MERGE>), topk_lds_bytes<ITEMS, 1>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 2, MERGE>), topk_lds_bytes<ITEMS, 2>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 4, MERGE>), topk_lds_bytes<ITEMS, 4>()) &&
-           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8, MERGE>), topk_lds_bytes<ITEMS, 8>());
+    return grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 1, MERGE>), topk_lds_bytes<ITEMS, 1, MERGE>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 2, MERGE>), topk_lds_bytes<ITEMS, 2, MERGE>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 4, MERGE>), topk_lds_bytes<ITEMS, 4, MERGE>()) &&
+           grant_lds(reinterpret_cast<const void*>(topk_kernel<ITEMS, 8, MERGE>), topk_lds_bytes<ITEMS, 8, MERGE>());
 }
 
 // Split-K partials of cusa_sparse_attn_noalloc: device memory that belongs to the library image,
@@ -568,7 +568,7 @@ struct TopkArgs {
 
 template <int ITEMS, int MTOP, bool MERGE>
 cusa_status launch_topk_m(const TopkArgs& a) {
-    const size_t shmem = topk_lds_bytes<ITEMS, MTOP>();
+    const size_t shmem = topk_lds_bytes<ITEMS, MTOP, MERGE>();
     launch(MERGE ? (a.filter.thr ? KID_TOPK_FILTERED : KID_TOPK_MERGE) : a.parts ? KID_TOPK_SLICE : KID_TOPK, topk_kernel<ITEMS, MTOP, MERGE>, a.grid, SEL_THREADS, shmem, a.s, a.P, a.ldp, a.seq_lens, a.rho_head, a.H, a.k,
            a.budget, a.window, a.raw, a.n_sink, a.parts, a.slice_len, a.n_slices, a.only_rows, a.filter);
     return launch_status();

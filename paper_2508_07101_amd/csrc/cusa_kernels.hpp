@@ -276,8 +276,11 @@ __host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
 }
 // 8-byte entries of LDS behind the sort buffer: the candidate list, later the quick ranking's segments
 // (mtop * 1024 composites) and its 2048 bin counters.
-__host__ __device__ constexpr int topk_area_entries(int items, int mtop) {
-    return topk_list_cap(items, mtop) > mtop * 1024 + 1024 ? topk_list_cap(items, mtop) : mtop * 1024 + 1024;
+__host__ __device__ constexpr int topk_area_entries(int items, int mtop, bool merge = false) {
+    int n = topk_list_cap(items, mtop) > mtop * 1024 + 1024 ? topk_list_cap(items, mtop) : mtop * 1024 + 1024;
+    // ranking all composites of a merge at once: items * 1024 segments entries and the bins, sort buffer included
+    if (merge && items * 1024 + 1024 - mtop * 1024 > n) n = items * 1024 + 1024 - mtop * 1024;
+    return n;
 }
 
 // Value of lane (l ^ STRIDE) for STRIDE < 64 without the LDS crossbar: DPP moves inside a 16-lane
@@ -314,6 +317,92 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
         case 16: return lane_xor<16>(v);
         default: return lane_xor<32>(v);
     }
+}
+
+// Ranks n composites (thread t holds entries t, t + 1024, ... in mine[]; all at or above the score s_lo)
+// and writes the picks ranked below k_out, rank-major (out[rank * H]) -- without a sorting network:
+// 2048 bins divide the score range evenly by value (monotone in the key, so bins are in rank order), a
+// counting sort puts every composite into its bin's segment, and inside a segment -- a few entries,
+// unless scores repeat -- a composite's rank is the number of entries that beat it.  The range is
+// [s_lo, s_lo + 6 x the mean excess over s_lo], not up to the best score: a few very large scores
+// (attention sinks, hot tokens) would otherwise stretch the bins over empty space and crowd the
+// rest; whatever lies above shares the first bin, which may hold more.  About a fifth of the
+// instructions of a sorting network.  Returns false, having written nothing, when a bin is crowded
+// (more than RMAX entries, RMAX_FIRST in the first: many equal scores) or the scores are not finite;
+// the caller then ranks another way.  seg: room for n composites; rbin: 2048 ints; scratch: as for
+// block_scan_excl.  Called by the whole workgroup.
+template <int NPT>
+__device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], int n, float s_lo, int k_out, uint64_t* seg,
+                                           int* rbin, int* scratch, int32_t* __restrict__ out, int H) {
+    constexpr int RBINS = 2048, RMAX = 32, RMAX_FIRST = 512;
+    __shared__ float rk_excess;
+    __shared__ int rk_crowd, rk_first;
+    const int tid = threadIdx.x;
+    __syncthreads();                                     // whatever the areas held before has been read
+    if (tid == 0) {
+        rk_excess = 0.0f;
+        rk_crowd = 0;
+    }
+    for (int i = tid; i < RBINS; i += SEL_THREADS) rbin[i] = 0;
+    float excess = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NPT; ++j)
+        if (tid + j * SEL_THREADS < n) excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) excess += __shfl_xor(excess, o);
+    __syncthreads();                                     // rk_excess, rbin are cleared
+    if (lane_id() == 0) atomicAdd(&rk_excess, excess);
+    __syncthreads();
+    const float range = 6.0f * rk_excess / (float)n;
+    bool quick = range > 0.0f && range < 3.0e38f;        // workgroup-uniform (not so: all scores equal, or not finite)
+    const float scale = quick ? (float)(RBINS - 1) / range : 0.0f;
+    auto bin_of = [&](uint64_t cv) {                     // bin 0 holds the best scores
+        const int up = (int)((key_score((uint32_t)(cv >> 32)) - s_lo) * scale);
+        return RBINS - 1 - (up < 0 ? 0 : up > RBINS - 1 ? RBINS - 1 : up);
+    };
+    int slot[NPT];
+    if (quick) {
+#pragma unroll
+        for (int j = 0; j < NPT; ++j)
+            if (tid + j * SEL_THREADS < n) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
+    }
+    __syncthreads();
+    {   // counts -> first indices (thread i owns bins 2i, 2i + 1); the most crowded bin
+        const int c0 = rbin[2 * tid], c1 = rbin[2 * tid + 1];
+        int total;
+        const int first = block_scan_excl(c0 + c1, scratch, &total);
+        int crowd = tid == 0 ? c1 : (c0 > c1 ? c0 : c1);   // bin 0 is looked at on its own
+        if (tid == 0) rk_first = c0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const int other = __shfl_xor(crowd, o);
+            crowd = other > crowd ? other : crowd;
+        }
+        if (lane_id() == 0) atomicMax(&rk_crowd, crowd);
+        rbin[2 * tid] = first;
+        rbin[2 * tid + 1] = first + c0;
+    }
+    __syncthreads();
+    quick = quick && rk_crowd <= RMAX && rk_first <= RMAX_FIRST;
+    if (!quick) return false;
+#pragma unroll
+    for (int j = 0; j < NPT; ++j)
+        if (tid + j * SEL_THREADS < n) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+        const int i = tid + j * SEL_THREADS;
+        if (i < n) {
+            const uint64_t cv = seg[i];
+            const int bn = bin_of(cv), lo = rbin[bn], hi = bn == RBINS - 1 ? n : rbin[bn + 1];
+            if (lo < k_out) {                            // the segment reaches into the ranks that are wanted
+                int rank = lo;
+                for (int q = lo; q < hi; ++q) rank += seg[q] > cv ? 1 : 0;
+                if (rank < k_out) out[(int64_t)rank * H] = (int32_t)~(uint32_t)cv;
+            }
+        }
+    }
+    return true;
 }
 
 // ITEMS == -1 is the streamed kernel in a register-lean form (half the keys in flight, compiled for two
@@ -379,6 +468,7 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
     auto key_of = [raw_keys](float v) { return raw_keys ? __float_as_uint(v) : score_key(v); };
     uint32_t keys[ITEMS > 0 ? ITEMS : 1];
     int pos_of[MERGE ? ITEMS : 1];                     // MERGE: the positions that come with the keys
+    int merge_n = 0;                                   // MERGE: the composites this workgroup ranks
     if constexpr (MERGE) {
         int n_cand = n_slices * k;
         const uint64_t* __restrict__ src = my_parts;
@@ -403,6 +493,7 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
             keys[i] = sl < n_cand ? (uint32_t)(cv >> 32) : 0u;
             pos_of[i] = (int)~(uint32_t)cv;
         }
+        merge_n = n_cand;
     } else if constexpr (ITEMS > 0) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
@@ -469,9 +560,24 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
     //    A streamed row keeps the maxima of 8 disjoint groups of the thread's candidates instead
     //    (one instruction per key): distinct candidates again, so the same argument holds, and
     //    with 8192 group maxima the bound is about as tight.
-    //    The candidates a filtered pass kept are few and most of them are among the k best: no bound
-    //    (d0 = 0) and no list for them.
+    //    The candidates a filtered pass kept are few and most of them are among the k best: they are
+    //    ranked as they are (quick_rank over all of them; only ranks below k_eff are written), and
+    //    selected first like any row only if that does not work out -- then without the bound (d0 = 0)
+    //    and the list.
     const bool direct = MERGE && flt.thr != nullptr;
+    if constexpr (MERGE && ITEMS <= 8) {              // (the lists of a filtered pass hold 4096 or 8192 composites)
+        if (direct) {
+            uint64_t mine[ITEMS];
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+                mine[i] = keys[i] != 0u ? ((uint64_t)keys[i] << 32) | (uint32_t)~(uint32_t)pos_of[i] : 0;
+            // every kept candidate is at or above the head's threshold
+            if (quick_rank<ITEMS>(mine, merge_n, key_score(flt.thr[(int64_t)b * H + h]), k_eff, sort_buf,
+                                  reinterpret_cast<int*>(sort_buf + ITEMS * SEL_THREADS), scratch,
+                                  rho_head + (int64_t)b * k * H + h, H))
+                return;
+        }
+    }
     constexpr int MG = ITEMS > 0 ? MTOP : ITEMS == -1 ? 4 : 8;
     uint32_t d0 = 0u;
     if (!direct) {
@@ -621,92 +727,18 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
         for (int i = threadIdx.x; i < k; i += SEL_THREADS) my_parts[i] = i < k_eff ? sort_buf[i] : 0;
         return;
     }
-    // 3a. The ranking, the quick way: 2048 bins divide the survivors' score range evenly by value
-    //     (monotone in the key, so bins are in rank order), a counting sort puts every survivor into its
-    //     bin's segment, and inside a segment -- a few entries, unless scores repeat -- a survivor's rank
-    //     is the number of entries that beat it.  Every survivor then writes its pick at its rank.  The
-    //     range is [score of T, that + 6 x the survivors' mean excess over it], not up to the best score:
-    //     a few very large scores (attention sinks, hot tokens) would otherwise stretch the bins over
-    //     empty space and crowd the rest; whatever lies above shares the first bin, which may hold more.
-    //     About a fifth of the instructions of the network below, which remains for rows with crowded
-    //     bins (many equal scores), non-finite scores and raw keys.
+    // 3a. The ranking, the quick way (quick_rank); the network below remains for rows with crowded bins
+    //     (many equal scores), non-finite scores and raw keys.
     if (!raw_keys) {
-        constexpr int RBINS = 2048, RMAX = 32, RMAX_FIRST = 512;   // bins; entries a bin / the first bin may hold
-        uint64_t* const seg = cand;                      // NSORT composites, ordered by bin
-        int* const rbin = reinterpret_cast<int*>(cand + NSORT);   // per bin: count, then first index
-        __shared__ float rk_excess;
-        __shared__ int rk_crowd, rk_first;
-        const int tid = threadIdx.x;
-        if (tid == 0) {
-            rk_excess = 0.0f;
-            rk_crowd = 0;
-        }
-        for (int i = tid; i < RBINS; i += SEL_THREADS) rbin[i] = 0;
         uint64_t mine[MTOP];
-        const float s_lo = key_score(sel_T);
-        float excess = 0.0f;
 #pragma unroll
         for (int j = 0; j < MTOP; ++j) {
-            const int i = tid + j * SEL_THREADS;
+            const int i = (int)threadIdx.x + j * SEL_THREADS;
             mine[j] = i < k_eff ? sort_buf[i] : 0;
-            if (i < k_eff) excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) excess += __shfl_xor(excess, o);
-        __syncthreads();                                 // rk_excess, rbin are cleared
-        if (lane_id() == 0) atomicAdd(&rk_excess, excess);
-        __syncthreads();
-        const float range = 6.0f * rk_excess / (float)k_eff;
-        bool quick = range > 0.0f && range < 3.0e38f;    // workgroup-uniform (not so: all scores equal, or not finite)
-        const float scale = quick ? (float)(RBINS - 1) / range : 0.0f;
-        auto bin_of = [&](uint64_t cv) {                 // bin 0 holds the best scores
-            const int up = (int)((key_score((uint32_t)(cv >> 32)) - s_lo) * scale);
-            return RBINS - 1 - (up < 0 ? 0 : up > RBINS - 1 ? RBINS - 1 : up);
-        };
-        int slot[MTOP];
-        if (quick) {
-#pragma unroll
-            for (int j = 0; j < MTOP; ++j)
-                if (tid + j * SEL_THREADS < k_eff) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
-        }
-        __syncthreads();
-        {   // counts -> first indices (thread i owns bins 2i, 2i + 1); the most crowded bin
-            const int c0 = rbin[2 * tid], c1 = rbin[2 * tid + 1];
-            int total;
-            const int first = block_scan_excl(c0 + c1, scratch, &total);
-            int crowd = tid == 0 ? c1 : (c0 > c1 ? c0 : c1);   // bin 0 is looked at on its own
-            if (tid == 0) rk_first = c0;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const int other = __shfl_xor(crowd, o);
-                crowd = other > crowd ? other : crowd;
-            }
-            if (lane_id() == 0) atomicMax(&rk_crowd, crowd);
-            rbin[2 * tid] = first;
-            rbin[2 * tid + 1] = first + c0;
-        }
-        __syncthreads();
-        quick = quick && rk_crowd <= RMAX && rk_first <= RMAX_FIRST;
-        if (quick) {
-#pragma unroll
-            for (int j = 0; j < MTOP; ++j)
-                if (tid + j * SEL_THREADS < k_eff) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
-            __syncthreads();
-            int32_t* __restrict__ out = rho_head + (int64_t)b * k * H + h;
-#pragma unroll
-            for (int j = 0; j < MTOP; ++j) {
-                const int i = tid + j * SEL_THREADS;
-                if (i < k_eff) {
-                    const uint64_t cv = seg[i];
-                    const int bn = bin_of(cv), lo = rbin[bn], hi = bn == RBINS - 1 ? k_eff : rbin[bn + 1];
-                    int rank = lo;
-                    for (int q = lo; q < hi; ++q) rank += seg[q] > cv ? 1 : 0;
-                    out[(int64_t)rank * H] = (int32_t)~(uint32_t)cv;
-                }
-            }
+        if (quick_rank<MTOP>(mine, k_eff, key_score(sel_T), k_eff, cand, reinterpret_cast<int*>(cand + NSORT), scratch,
+                             rho_head + (int64_t)b * k * H + h, H))
             return;
-        }
-        __syncthreads();                                 // the bins' area is the list's again below (not used any more)
     }
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
     __syncthreads();
