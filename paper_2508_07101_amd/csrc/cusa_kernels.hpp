@@ -319,7 +319,7 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
     }
 }
 
-// Ranks n composites (thread t holds entries t, t + 1024, ... in mine[]; all at or above the score s_lo)
+// Ranks the composites that the threads hold in mine[] (zero: none; all at or above the score s_lo)
 // and writes the picks ranked below k_out, rank-major (out[rank * H]) -- without a sorting network:
 // 2048 bins divide the score range evenly by value (monotone in the key, so bins are in rank order), a
 // counting sort puts every composite into its bin's segment, and inside a segment -- a few entries,
@@ -328,32 +328,45 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
 // (attention sinks, hot tokens) would otherwise stretch the bins over empty space and crowd the
 // rest; whatever lies above shares the first bin, which may hold more.  About a fifth of the
 // instructions of a sorting network.  Returns false, having written nothing, when a bin is crowded
-// (more than RMAX entries, RMAX_FIRST in the first: many equal scores) or the scores are not finite;
-// the caller then ranks another way.  seg: room for n composites; rbin: 2048 ints; scratch: as for
+// (more than RMAX entries among the bins that hold wanted ranks, RMAX_FIRST in the first: many equal
+// scores) or the scores are not finite;
+// the caller then ranks another way.  seg: room for all the composites; rbin: 2048 ints; scratch: as for
 // block_scan_excl.  Called by the whole workgroup.
 template <int NPT>
-__device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], int n, float s_lo, int k_out, uint64_t* seg,
-                                           int* rbin, int* scratch, int32_t* __restrict__ out, int H) {
+__device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_lo, int k_out, uint64_t* seg, int* rbin,
+                                           int* scratch, int32_t* __restrict__ out, int H) {
     constexpr int RBINS = 2048, RMAX = 32, RMAX_FIRST = 512;
     __shared__ float rk_excess;
-    __shared__ int rk_crowd, rk_first;
+    __shared__ int rk_crowd, rk_first, rk_n;
     const int tid = threadIdx.x;
     __syncthreads();                                     // whatever the areas held before has been read
     if (tid == 0) {
         rk_excess = 0.0f;
-        rk_crowd = 0;
+        rk_crowd = rk_n = 0;
     }
     for (int i = tid; i < RBINS; i += SEL_THREADS) rbin[i] = 0;
     float excess = 0.0f;
+    int n_mine = 0;
 #pragma unroll
-    for (int j = 0; j < NPT; ++j)
-        if (tid + j * SEL_THREADS < n) excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
+    for (int j = 0; j < NPT; ++j) {
+        if (mine[j] != 0) {
+            excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
+            ++n_mine;
+        }
+    }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) excess += __shfl_xor(excess, o);
-    __syncthreads();                                     // rk_excess, rbin are cleared
-    if (lane_id() == 0) atomicAdd(&rk_excess, excess);
+    for (int o = 32; o > 0; o >>= 1) {
+        excess += __shfl_xor(excess, o);
+        n_mine += __shfl_xor(n_mine, o);
+    }
+    __syncthreads();                                     // the counters and rbin are cleared
+    if (lane_id() == 0) {
+        atomicAdd(&rk_excess, excess);
+        atomicAdd(&rk_n, n_mine);
+    }
     __syncthreads();
-    const float range = 6.0f * rk_excess / (float)n;
+    const int n = rk_n;
+    const float range = n > 0 ? 6.0f * rk_excess / (float)n : 0.0f;
     bool quick = range > 0.0f && range < 3.0e38f;        // workgroup-uniform (not so: all scores equal, or not finite)
     const float scale = quick ? (float)(RBINS - 1) / range : 0.0f;
     auto bin_of = [&](uint64_t cv) {                     // bin 0 holds the best scores
@@ -364,14 +377,17 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], int n, f
     if (quick) {
 #pragma unroll
         for (int j = 0; j < NPT; ++j)
-            if (tid + j * SEL_THREADS < n) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
+            if (mine[j] != 0) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
     }
     __syncthreads();
     {   // counts -> first indices (thread i owns bins 2i, 2i + 1); the most crowded bin
         const int c0 = rbin[2 * tid], c1 = rbin[2 * tid + 1];
         int total;
         const int first = block_scan_excl(c0 + c1, scratch, &total);
-        int crowd = tid == 0 ? c1 : (c0 > c1 ? c0 : c1);   // bin 0 is looked at on its own
+        // only segments that reach into the wanted ranks are walked: the others may be crowded; bin 0 is
+        // looked at on its own
+        int crowd = first + c0 < k_out ? c1 : 0;
+        if (tid != 0 && first < k_out && c0 > crowd) crowd = c0;
         if (tid == 0) rk_first = c0;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -387,20 +403,16 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], int n, f
     if (!quick) return false;
 #pragma unroll
     for (int j = 0; j < NPT; ++j)
-        if (tid + j * SEL_THREADS < n) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
+        if (mine[j] != 0) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
     __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-        const int i = tid + j * SEL_THREADS;
-        if (i < n) {
-            const uint64_t cv = seg[i];
-            const int bn = bin_of(cv), lo = rbin[bn], hi = bn == RBINS - 1 ? n : rbin[bn + 1];
-            if (lo < k_out) {                            // the segment reaches into the ranks that are wanted
-                int rank = lo;
-                for (int q = lo; q < hi; ++q) rank += seg[q] > cv ? 1 : 0;
-                if (rank < k_out) out[(int64_t)rank * H] = (int32_t)~(uint32_t)cv;
-            }
-        }
+    // the composites ranked below k_out lie in the segments' first k_out entries or just behind them
+    for (int i = tid; i < n; i += SEL_THREADS) {
+        const uint64_t cv = seg[i];
+        const int bn = bin_of(cv), lo = rbin[bn], hi = bn == RBINS - 1 ? n : rbin[bn + 1];
+        if (lo >= k_out) break;                          // (segments are in rank order: nothing wanted from here on)
+        int rank = lo;
+        for (int q = lo; q < hi; ++q) rank += seg[q] > cv ? 1 : 0;
+        if (rank < k_out) out[(int64_t)rank * H] = (int32_t)~(uint32_t)cv;
     }
     return true;
 }
@@ -415,7 +427,7 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], int n, f
 // with zeros, in parts[row][slice][k]; the k best of a row are among the k best of its slices, so a
 // second launch (MERGE) selects and ranks among those n_slices * k composites instead of the row.
 template <int ITEMS, int MTOP, bool MERGE = false>
-__global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)) && MTOP <= 4) ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
+__global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 && MTOP <= 4) || (MERGE && ITEMS <= 4 && MTOP <= 2)) ? 8 : 4) void topk_kernel(const float* __restrict__ P, int64_t ldp,
                                                             const int32_t* __restrict__ seq_lens,
                                                             int32_t* __restrict__ rho_head, int H, int k,
                                                             int budget, int window, int raw_keys, int n_sink,
@@ -468,7 +480,6 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
     auto key_of = [raw_keys](float v) { return raw_keys ? __float_as_uint(v) : score_key(v); };
     uint32_t keys[ITEMS > 0 ? ITEMS : 1];
     int pos_of[MERGE ? ITEMS : 1];                     // MERGE: the positions that come with the keys
-    int merge_n = 0;                                   // MERGE: the composites this workgroup ranks
     if constexpr (MERGE) {
         int n_cand = n_slices * k;
         const uint64_t* __restrict__ src = my_parts;
@@ -486,14 +497,52 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
             }
             src = flt.cand + row * flt.cap;
         }
+        uint64_t mcv[ITEMS];                           // this thread's composites (zero: none)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int sl = i * SEL_THREADS + threadIdx.x;
             const uint64_t cv = src[sl < n_cand ? sl : n_cand - 1];
-            keys[i] = sl < n_cand ? (uint32_t)(cv >> 32) : 0u;
-            pos_of[i] = (int)~(uint32_t)cv;
+            mcv[i] = sl < n_cand ? cv : 0;
         }
-        merge_n = n_cand;
+        // These composites are few and most of them among the k best, so they are first ranked as they are:
+        // quick_rank over all of them, of which only the ranks below k_eff are written.  A filtered pass's
+        // candidates are all at or above the head's threshold; the slices' picks (zeros where a slice had
+        // fewer than k) start at the lowest of their scores.  If that does not work out (crowded bins) they
+        // are selected and sorted like any row.
+        if constexpr (ITEMS <= 8 || MTOP <= 4) {       // (what fits the register file)
+            if (!raw_keys) {
+                float s_lo;
+                if (flt.thr) {
+                    s_lo = key_score(flt.thr[(int64_t)b * H + h]);
+                } else {
+                    __shared__ uint32_t merge_lowest;
+                    uint32_t lowest = 0xffffffffu;
+#pragma unroll
+                    for (int i = 0; i < ITEMS; ++i) {
+                        const uint32_t key = (uint32_t)(mcv[i] >> 32);
+                        if (mcv[i] != 0 && key < lowest) lowest = key;
+                    }
+                    if (threadIdx.x == 0) merge_lowest = 0xffffffffu;
+                    __syncthreads();
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) {
+                        const uint32_t other = __shfl_xor(lowest, o);
+                        lowest = other < lowest ? other : lowest;
+                    }
+                    if (lane_id() == 0) atomicMin(&merge_lowest, lowest);
+                    __syncthreads();
+                    s_lo = key_score(merge_lowest);
+                }
+                if (quick_rank<ITEMS>(mcv, s_lo, k_eff, sort_buf, reinterpret_cast<int*>(sort_buf + ITEMS * SEL_THREADS),
+                                      scratch, rho_head + (int64_t)b * k * H + h, H))
+                    return;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            keys[i] = (uint32_t)(mcv[i] >> 32);
+            pos_of[i] = (int)~(uint32_t)mcv[i];
+        }
     } else if constexpr (ITEMS > 0) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
@@ -560,24 +609,9 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
     //    A streamed row keeps the maxima of 8 disjoint groups of the thread's candidates instead
     //    (one instruction per key): distinct candidates again, so the same argument holds, and
     //    with 8192 group maxima the bound is about as tight.
-    //    The candidates a filtered pass kept are few and most of them are among the k best: they are
-    //    ranked as they are (quick_rank over all of them; only ranks below k_eff are written), and
-    //    selected first like any row only if that does not work out -- then without the bound (d0 = 0)
-    //    and the list.
+    //    The candidates a filtered pass kept (when ranking them as they are did not work out, above): no
+    //    bound (d0 = 0) and no list for them.
     const bool direct = MERGE && flt.thr != nullptr;
-    if constexpr (MERGE && ITEMS <= 8) {              // (the lists of a filtered pass hold 4096 or 8192 composites)
-        if (direct) {
-            uint64_t mine[ITEMS];
-#pragma unroll
-            for (int i = 0; i < ITEMS; ++i)
-                mine[i] = keys[i] != 0u ? ((uint64_t)keys[i] << 32) | (uint32_t)~(uint32_t)pos_of[i] : 0;
-            // every kept candidate is at or above the head's threshold
-            if (quick_rank<ITEMS>(mine, merge_n, key_score(flt.thr[(int64_t)b * H + h]), k_eff, sort_buf,
-                                  reinterpret_cast<int*>(sort_buf + ITEMS * SEL_THREADS), scratch,
-                                  rho_head + (int64_t)b * k * H + h, H))
-                return;
-        }
-    }
     constexpr int MG = ITEMS > 0 ? MTOP : ITEMS == -1 ? 4 : 8;
     uint32_t d0 = 0u;
     if (!direct) {
@@ -736,7 +770,7 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 || (MERGE && ITEMS <= 4)
             const int i = (int)threadIdx.x + j * SEL_THREADS;
             mine[j] = i < k_eff ? sort_buf[i] : 0;
         }
-        if (quick_rank<MTOP>(mine, k_eff, key_score(sel_T), k_eff, cand, reinterpret_cast<int*>(cand + NSORT), scratch,
+        if (quick_rank<MTOP>(mine, key_score(sel_T), k_eff, cand, reinterpret_cast<int*>(cand + NSORT), scratch,
                              rho_head + (int64_t)b * k * H + h, H))
             return;
     }
