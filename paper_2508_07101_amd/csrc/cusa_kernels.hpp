@@ -274,10 +274,12 @@ __device__ __forceinline__ int wave_reserve(int mine, int* counter) {
 __host__ __device__ constexpr int topk_list_cap(int items, int mtop) {
     return (items > 0 && items < 8) ? 0 : (mtop <= 2 ? 6144 : 10240);
 }
-// 8-byte entries of LDS behind the sort buffer: the candidate list, later the quick ranking's segments
-// (mtop * 1024 composites) and its 2048 bin counters.
+// 8-byte entries of LDS behind the sort buffer: the candidate list or the quick ranking's segments, and
+// behind them its 2048 bin counters.
 __host__ __device__ constexpr int topk_area_entries(int items, int mtop, bool merge = false) {
-    int n = topk_list_cap(items, mtop) > mtop * 1024 + 1024 ? topk_list_cap(items, mtop) : mtop * 1024 + 1024;
+    int n = topk_list_cap(items, mtop) + 1024 > mtop * 1024 + 1024 ? topk_list_cap(items, mtop) + 1024 : mtop * 1024 + 1024;
+    // short rows (no list): room to rank all their candidates at once
+    if (items > 0 && items < 8 && items * 1024 + 1024 > n) n = items * 1024 + 1024;
     // ranking all composites of a merge at once: items * 1024 segments entries and the bins, sort buffer included
     if (merge && items * 1024 + 1024 - mtop * 1024 > n) n = items * 1024 + 1024 - mtop * 1024;
     return n;
@@ -319,7 +321,7 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
     }
 }
 
-// Ranks the composites that the threads hold in mine[] (zero: none; all at or above the score s_lo)
+// Ranks the composites mine(0) .. mine(NPT - 1) of every thread (zero: none; all at or above the score s_lo)
 // and writes the picks ranked below k_out, rank-major (out[rank * H]) -- without a sorting network:
 // 2048 bins divide the score range evenly by value (monotone in the key, so bins are in rank order), a
 // counting sort puts every composite into its bin's segment, and inside a segment -- a few entries,
@@ -330,10 +332,10 @@ __device__ __forceinline__ uint32_t lane_xor_any(uint32_t v, int stride) {
 // instructions of a sorting network.  Returns false, having written nothing, when a bin is crowded
 // (more than RMAX entries among the bins that hold wanted ranks, RMAX_FIRST in the first: many equal
 // scores) or the scores are not finite;
-// the caller then ranks another way.  seg: room for all the composites; rbin: 2048 ints; scratch: as for
+// the caller then ranks another way.  seg: room for seg_cap composites (more: false); rbin: 2048 ints; scratch: as for
 // block_scan_excl.  Called by the whole workgroup.
-template <int NPT>
-__device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_lo, int k_out, uint64_t* seg, int* rbin,
+template <int NPT, typename Mine>
+__device__ __forceinline__ bool quick_rank(Mine mine, float s_lo, int k_out, uint64_t* seg, int seg_cap, int* rbin,
                                            int* scratch, int32_t* __restrict__ out, int H) {
     constexpr int RBINS = 2048, RMAX = 32, RMAX_FIRST = 512;
     __shared__ float rk_excess;
@@ -349,8 +351,8 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_
     int n_mine = 0;
 #pragma unroll
     for (int j = 0; j < NPT; ++j) {
-        if (mine[j] != 0) {
-            excess += key_score((uint32_t)(mine[j] >> 32)) - s_lo;
+        if (mine(j) != 0) {
+            excess += key_score((uint32_t)(mine(j) >> 32)) - s_lo;
             ++n_mine;
         }
     }
@@ -367,7 +369,8 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_
     __syncthreads();
     const int n = rk_n;
     const float range = n > 0 ? 6.0f * rk_excess / (float)n : 0.0f;
-    bool quick = range > 0.0f && range < 3.0e38f;        // workgroup-uniform (not so: all scores equal, or not finite)
+    // workgroup-uniform (not so: all scores equal, or not finite, or more composites than seg holds)
+    bool quick = range > 0.0f && range < 3.0e38f && n <= seg_cap;
     const float scale = quick ? (float)(RBINS - 1) / range : 0.0f;
     auto bin_of = [&](uint64_t cv) {                     // bin 0 holds the best scores
         const int up = (int)((key_score((uint32_t)(cv >> 32)) - s_lo) * scale);
@@ -377,7 +380,7 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_
     if (quick) {
 #pragma unroll
         for (int j = 0; j < NPT; ++j)
-            if (mine[j] != 0) slot[j] = atomicAdd(&rbin[bin_of(mine[j])], 1);
+            if (mine(j) != 0) slot[j] = atomicAdd(&rbin[bin_of(mine(j))], 1);
     }
     __syncthreads();
     {   // counts -> first indices (thread i owns bins 2i, 2i + 1); the most crowded bin
@@ -403,7 +406,7 @@ __device__ __forceinline__ bool quick_rank(const uint64_t (&mine)[NPT], float s_
     if (!quick) return false;
 #pragma unroll
     for (int j = 0; j < NPT; ++j)
-        if (mine[j] != 0) seg[rbin[bin_of(mine[j])] + slot[j]] = mine[j];
+        if (mine(j) != 0) seg[rbin[bin_of(mine(j))] + slot[j]] = mine(j);
     __syncthreads();
     // the composites ranked below k_out lie in the segments' first k_out entries or just behind them
     for (int i = tid; i < n; i += SEL_THREADS) {
@@ -533,8 +536,9 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 && MTOP <= 4) || (MERGE 
                     __syncthreads();
                     s_lo = key_score(merge_lowest);
                 }
-                if (quick_rank<ITEMS>(mcv, s_lo, k_eff, sort_buf, reinterpret_cast<int*>(sort_buf + ITEMS * SEL_THREADS),
-                                      scratch, rho_head + (int64_t)b * k * H + h, H))
+                if (quick_rank<ITEMS>([&](int j) { return mcv[j]; }, s_lo, k_eff, sort_buf, ITEMS * SEL_THREADS,
+                                      reinterpret_cast<int*>(sort_buf + ITEMS * SEL_THREADS), scratch,
+                                      rho_head + (int64_t)b * k * H + h, H))
                     return;
             }
         }
@@ -647,6 +651,22 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 && MTOP <= 4) || (MERGE 
     pick_digit<2048>(hist, scratch, &st, 21);
     d0 = st.prefix >> 21;
     __syncthreads();
+    }
+    //    With the keys in registers, what lies at or above the bound -- typically 1.3 to 2 times k
+    //    candidates -- is ranked as it is (quick_rank: only the segments that reach into the first k_eff
+    //    ranks are walked); the selection below runs only if that does not work out.
+    if constexpr (ITEMS > 0 && ITEMS <= 16 && !MERGE) {   // (32 keys per thread leave no registers for it)
+        if (!slice && !raw_keys && d0 > 0u) {
+            const uint32_t bound = d0 << 21;
+            auto mine = [&](int i) -> uint64_t {
+                const int t = t_lo + i * SEL_THREADS + (int)threadIdx.x;
+                return keys[i] >= bound ? ((uint64_t)keys[i] << 32) | (uint32_t)~(uint32_t)t : 0;
+            };
+            constexpr int SEGS = topk_area_entries(ITEMS, MTOP) - 1024;
+            if (quick_rank<ITEMS>(mine, key_score(bound), k_eff, cand, SEGS, reinterpret_cast<int*>(cand + SEGS), scratch,
+                                  rho_head + (int64_t)b * k * H + h, H))
+                return;
+        }
     }
     // 1-3 for candidates delivered by scan_fn: the remaining digits of the k_eff-th best score key
     // T (its top digit is already in st), the position bound among the keys equal to T when they
@@ -770,8 +790,8 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 && MTOP <= 4) || (MERGE 
             const int i = (int)threadIdx.x + j * SEL_THREADS;
             mine[j] = i < k_eff ? sort_buf[i] : 0;
         }
-        if (quick_rank<MTOP>(mine, key_score(sel_T), k_eff, cand, reinterpret_cast<int*>(cand + NSORT), scratch,
-                             rho_head + (int64_t)b * k * H + h, H))
+        if (quick_rank<MTOP>([&](int j) { return mine[j]; }, key_score(sel_T), k_eff, cand, NSORT,
+                             reinterpret_cast<int*>(cand + NSORT), scratch, rho_head + (int64_t)b * k * H + h, H))
             return;
     }
     for (int i = k_eff + threadIdx.x; i < NSORT; i += SEL_THREADS) sort_buf[i] = 0;
