@@ -768,6 +768,23 @@ __global__ __launch_bounds__(SEL_THREADS, ((ITEMS == -1 && MTOP <= 4) || (MERGE 
     }
     if (listed) {
         const int n = n_list;
+        // Rows too long for the ranking from registers above: the list holds exactly what lies at or above
+        // the bound, so it is ranked as it is (the entries move to registers first: the segments take the
+        // list's place, but only once the attempt is known to work out).
+        if constexpr ((ITEMS > 16 || ITEMS == 0) && CAP > 0) {   // (not the lean streamed form: 64 registers)
+            if (!slice && !raw_keys && d0 > 0u) {
+                constexpr int LPT = CAP / SEL_THREADS;
+                uint64_t lv[LPT];
+#pragma unroll
+                for (int j = 0; j < LPT; ++j) {
+                    const int i = (int)threadIdx.x + j * SEL_THREADS;
+                    lv[j] = i < n ? cand[i] : 0;
+                }
+                if (quick_rank<LPT>([&](int j) { return lv[j]; }, key_score(d0 << 21), k_eff, cand, CAP,
+                                    reinterpret_cast<int*>(cand + CAP), scratch, rho_head + (int64_t)b * k * H + h, H))
+                    return;
+            }
+        }
         finish([&](auto f) {
             for (int i = threadIdx.x; i < n; i += SEL_THREADS) {
                 const uint64_t cv = cand[i];
