@@ -1,8 +1,9 @@
 // Device code of libcusa: gfx950 kernels for the CUSA decode hot path.
 //
-//   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on
-//                       order-preserving keys, then a bitonic sort held in registers
-//                       (lane exchanges by DPP / permlane swaps, LDS across waves)
+//   topk_kernel         per-head ranked top-k (Sec. 3.2): radix select on order-preserving keys;
+//                       the ranking by a counting sort over value bins (quick_rank) or, where
+//                       scores crowd, a bitonic sort held in registers (lane exchanges by DPP /
+//                       permlane swaps, LDS across waves)
 //   union_kernel        cross-head union, first-occurrence global rank, cut at
 //                       K-W, recency window (Sec. 3.2, 3.3) -> ascending rho
 //   attn_kernel         split-K flash-decode over all tokens or over rho
@@ -12,6 +13,9 @@
 //                       products accumulated by k = 1 MFMA in column order
 //   sample_threshold_kernel   per-head thresholds from a sample of the scores (filtered selection)
 //   attn_reduce_kernel  merges the split-K partials and writes bf16
+//   per_head_rho_kernel, rank_aggregate_kernel, recall_kernel   the head-to-head variant, the other
+//                       two readings of the global ranking, the recall of Eq. 3
+//   probe_*_kernel      traffic probes (benchmark support)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
